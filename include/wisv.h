@@ -1,0 +1,210 @@
+/*
+ * wisv.h - C ABI of the edge-side verification round of WISV
+ * (Wireless-Informed Semantic Verification for distributed speculative decoding).
+ *
+ * One call to wisv_verify_round() is one pass of Algorithm 1's edge-side body for a batch
+ * of independent device streams:
+ *
+ *   Verify    the target decoder forwards each stream's block of K drafted tokens against
+ *             that stream's KV cache, giving greedy target tokens and final hidden states
+ *             h^T (Sec. III-A step 2; Alg. 1 "Verify");
+ *   Localize  mismatch set S = { j : draft_j != target greedy token for position j }
+ *             (Sec. III-A step 2, Sec. V-C; Alg. 1 "Localize");
+ *   Head      the CSI-aware decision head scores positions from z = [h^D ; h^T ; c]:
+ *             s = w2 . act(W1 z + b1) + b2, p_rej = sigmoid(s) (Sec. V-A, eqs. feature_concat,
+ *             head_forward, mlp_form), with drafter hidden states h^D uploaded for every
+ *             position (full-hidden, FH) or only for S (selective-hidden, SH) (Sec. III-B);
+ *   Decide    thresholding (eq. threshold), earliest rejected position, accepted prefix and
+ *             the correction token, or the bonus token on full acceptance
+ *             (Sec. III-A step 4; Alg. 1 last block).
+ *
+ * Polarity.  The paper's head emits a rejection probability p_rej and rejects when
+ * p_rej >= tau_paper.  This interface reports p_accept = 1 - p_rej and ACCEPTS a gated
+ * position when p_accept >= tau, i.e. tau = 1 - tau_paper: tau <= 0 accepts every block in
+ * full, tau > 1 rejects every gated position (plain greedy verification, Sec. II-A).
+ *
+ * The target is a Llama-style decoder (RMSNorm, rotary embedding with rotate-half pairing,
+ * grouped-query attention, SwiGLU, no biases).  Everything runs on one GPU (gfx950); the
+ * library needs the HIP runtime and a device and has no CPU fallback.
+ *
+ * General rules
+ *   - every function returns a wisv_status (0 = success, negative = error); nothing throws,
+ *     aborts or prints.  After an error the outputs are untouched and wisv_last_error()
+ *     describes it.  Per-stream soft conditions are reported in wisv_round_out.status.
+ *   - "device pointer" = memory of the ctx's GPU; "host pointer" = ordinary process memory.
+ *   - a ctx is used by one host thread at a time; the library keeps no global state.
+ *   - identical inputs give identical bits (no floating-point atomics anywhere).
+ */
+#ifndef WISV_H
+#define WISV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct wisv_ctx wisv_ctx; /* opaque */
+
+typedef enum {
+    WISV_OK = 0,
+    WISV_EINVAL = -1,      /* bad argument or configuration */
+    WISV_ENOMEM = -2,      /* host or device allocation failed */
+    WISV_EHIP = -3,        /* a HIP runtime call failed */
+    WISV_ESTATE = -4,      /* stream state does not allow the call (e.g. cache full) */
+    WISV_EUNSUPPORTED = -5 /* valid request this build cannot serve */
+} wisv_status;
+
+typedef enum { WISV_F32 = 0, WISV_BF16 = 1 } wisv_dtype;
+typedef enum { WISV_PROTO_FH = 0, WISV_PROTO_SH = 1 } wisv_proto; /* Sec. III-B */
+typedef enum { WISV_ACT_SILU = 0, WISV_ACT_RELU = 1 /* eq. mlp_form */ } wisv_act;
+
+/* wisv_round_in.flags */
+#define WISV_FLAG_GATE_ALL 1u    /* the head gates every position, not only S (needs h^D everywhere) */
+#define WISV_FLAG_NO_COMMIT 2u   /* leave kv_len / pred_next of the streams unchanged */
+#define WISV_FLAG_DEVICE_IO 4u   /* all round_in / round_out pointers are device pointers; enqueue only */
+#define WISV_FLAG_KEEP_LOGITS 8u /* also materialise fp32 logits for wisv_debug_copy (debug, slow) */
+
+/* wisv_round_out.status bits */
+#define WISV_STATUS_MISSING_HIDDEN 1u /* a gated position had no h^D row: it was rejected */
+
+#define WISV_MAX_K 16 /* largest draft block per stream */
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff, vocab;
+    float rms_eps, rope_theta;
+    int32_t dtype;   /* wisv_dtype: storage type of every weight, of the KV cache and of h^D.
+                        Arithmetic: WISV_F32 all float; WISV_BF16 bf16 matrix-product operands,
+                        float accumulation, float residual stream / softmax / decision head. */
+    int32_t d_draft; /* width of a drafter hidden state h^D */
+    int32_t d_csi;   /* number of CSI features (1..16) */
+    int32_t d_head_hidden; /* d_J, hidden width of the decision head */
+    int32_t head_act;      /* wisv_act */
+    int32_t max_batch;     /* number of stream slots (each owns a KV cache of max_ctx positions) */
+    int32_t max_ctx;       /* KV positions per slot, drafted block included */
+    int32_t max_k;         /* largest k of a round, <= WISV_MAX_K */
+    int32_t device_id;
+    void *hip_stream; /* hipStream_t all work is enqueued on (borrowed; NULL = the null stream) */
+    void *kv_cache;   /* device pointer to borrowed cache memory, or NULL: the ctx allocates.
+                         Layout [n_layers][max_batch][2 (K,V)][n_kv_heads][max_ctx][head_dim], dtype as above */
+    size_t kv_bytes;  /* size of kv_cache when borrowed (must cover the layout) */
+} wisv_config;
+
+/* Model parameters: device pointers, canonical [out_features, in_features] row-major tensors of
+ * config.dtype, borrowed for the duration of wisv_ctx_create only (the ctx keeps private,
+ * re-tiled copies).  Per-layer members are host arrays of n_layers device pointers. */
+typedef struct {
+    const void *embed;      /* [vocab, d_model] */
+    const void *lm_head;    /* [vocab, d_model] */
+    const void *final_norm; /* [d_model] */
+    const void *const *attn_norm; /* [d_model] */
+    const void *const *wq;        /* [n_heads*head_dim, d_model] */
+    const void *const *wk;        /* [n_kv_heads*head_dim, d_model] */
+    const void *const *wv;        /* [n_kv_heads*head_dim, d_model] */
+    const void *const *wo;        /* [d_model, n_heads*head_dim] */
+    const void *const *ffn_norm;  /* [d_model] */
+    const void *const *w_gate;    /* [d_ff, d_model] */
+    const void *const *w_up;      /* [d_ff, d_model] */
+    const void *const *w_down;    /* [d_model, d_ff] */
+    const void *head_w1; /* [d_J, d_draft + d_model + d_csi], columns ordered [h^D ; h^T ; c] (eq. feature_concat) */
+    const void *head_b1; /* [d_J] */
+    const void *head_w2; /* [d_J] */
+    const void *head_b2; /* [1] */
+} wisv_weights;
+
+/* One round for `batch` streams, k drafted tokens each.  Host pointers unless WISV_FLAG_DEVICE_IO. */
+typedef struct {
+    int32_t batch; /* 1..max_batch */
+    int32_t k;     /* 1..max_k */
+    const int32_t *stream_ids;   /* [batch] distinct slot indices in [0, max_batch) */
+    const int32_t *draft_tokens; /* [batch*k] drafted token ids */
+    const int32_t *proto;        /* [batch] wisv_proto of each stream */
+    const void *hd;         /* uploaded drafter hidden states [n_hd, d_draft] of config.dtype (may be NULL if n_hd == 0) */
+    const int32_t *hd_row;  /* [batch*k] row of hd holding position (b, j), or -1 = not uploaded;
+                               NULL = identity map (row b*k + j; needs n_hd == batch*k) */
+    int32_t n_hd;
+    const float *csi; /* [batch, d_csi] CSI feature vector c^r of each stream, float */
+    const float *tau; /* [batch] accept threshold of each stream */
+    uint32_t flags;
+} wisv_round_in;
+
+/* Caller-owned, caller-sized outputs.  The first three are required. */
+typedef struct {
+    int32_t *accepted_len;     /* [batch] A in [0, k]: drafts before the earliest rejected position */
+    int32_t *correction_token; /* [batch] target greedy token for position A (the bonus token when A == k) */
+    float *p_accept;           /* [batch*k] 1 - sigmoid(s) where the head was evaluated (FH: every position with
+                                  an h^D row; SH: mismatch positions with an h^D row), 1.0 elsewhere */
+    int32_t *target_argmax;    /* [batch*(k+1)] target greedy tokens for positions 0..k, or NULL */
+    uint32_t *mismatch_mask;   /* [batch] bit j set <=> position j is in S (the SH request), or NULL */
+    uint32_t *status;          /* [batch] WISV_STATUS_* bits, or NULL */
+} wisv_round_out;
+
+/* Builds a context: validates the configuration (before any GPU call), allocates the KV cache
+ * (unless borrowed), scratch and rotary tables on config.device_id, and copies the weights into
+ * private layouts.  On failure *out is NULL and, when `err` is non-NULL, a message of at most
+ * err_len bytes (NUL included) is written there. */
+int wisv_ctx_create(const wisv_config *config, const wisv_weights *weights, wisv_ctx **out,
+                    char *err, size_t err_len);
+
+/* One verification round (see the top of this file).  Host-pointer mode copies the inputs in,
+ * runs the round and returns after the results are in the caller's buffers.  With
+ * WISV_FLAG_DEVICE_IO the round is only enqueued on the ctx's stream.
+ * Unless WISV_FLAG_NO_COMMIT: the K/V rows of the k drafted tokens stay in the cache, each
+ * stream's length grows by A (rows beyond are dead and overwritten by the next round) and its
+ * pred_next becomes the correction token (Sec. IV-B: the state recursion of the committed prefix).
+ * The target's greedy token for draft position 0 is the stream's pred_next state. */
+int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_round_out *out);
+
+/* Frees everything the ctx owns (not the borrowed stream / cache).  NULL is a no-op. */
+int wisv_destroy(wisv_ctx *ctx);
+
+/* --- state helpers --------------------------------------------------------------------------- */
+
+/* Runs the target over n prompt tokens (host pointer) of an empty or partly filled slot with the
+ * round's own kernels, appends their K/V, and sets pred_next to the greedy token after the last. */
+int wisv_prefill(wisv_ctx *ctx, int32_t stream_id, const int32_t *tokens, int32_t n);
+
+/* Sets a slot's cached length and pred_next directly (cache contents: wisv_kv_import). */
+int wisv_set_state(wisv_ctx *ctx, int32_t stream_id, int32_t kv_len, int32_t pred_next);
+
+/* Reads a slot's cached length and pred_next (synchronises the stream). */
+int wisv_get_state(wisv_ctx *ctx, int32_t stream_id, int32_t *kv_len, int32_t *pred_next);
+
+/* Copies positions [0, len) of one (slot, layer) between the cache and host buffers laid out
+ * [n_kv_heads][len][head_dim] in config.dtype.  K is stored rotated (rotary embedding applied). */
+int wisv_kv_import(wisv_ctx *ctx, int32_t stream_id, int32_t layer, const void *host_k,
+                   const void *host_v, int32_t len);
+int wisv_kv_export(wisv_ctx *ctx, int32_t stream_id, int32_t layer, void *host_k, void *host_v,
+                   int32_t len);
+
+/* --- diagnostics ----------------------------------------------------------------------------- */
+
+typedef enum {
+    WISV_DBG_HIDDEN = 0, /* float [batch*k, d_model]: h^T of the last round */
+    WISV_DBG_LOGITS = 1  /* float [batch*k, vocab]: logits of the last round run with WISV_FLAG_KEEP_LOGITS */
+} wisv_debug_what;
+
+/* Copies a diagnostic buffer of the last round to host memory (synchronises). */
+int wisv_debug_copy(wisv_ctx *ctx, int32_t what, void *host_dst, size_t bytes);
+
+/* Duration in milliseconds of the GPU work of the last wisv_verify_round, measured with HIP events
+ * recorded on the ctx's stream around the round's kernels (waits for the round to finish). */
+int wisv_last_round_ms(wisv_ctx *ctx, float *ms);
+
+/* Per-kernel timing.  While enabled, every kernel launch of a round is bracketed by a HIP event pair
+ * on the ctx's stream.  wisv_profile_collect() waits for the stream and adds the elapsed times of the
+ * launches since the last collect to per-class totals; wisv_profile_read() returns one class's name
+ * (static string), accumulated milliseconds and launch count.  Enabling or disabling resets the totals.
+ * kclass runs from 0 until wisv_profile_read() returns WISV_EINVAL. */
+int wisv_profile_enable(wisv_ctx *ctx, int32_t on);
+int wisv_profile_collect(wisv_ctx *ctx);
+int wisv_profile_read(wisv_ctx *ctx, int32_t kclass, const char **name, double *total_ms, int64_t *launches);
+
+/* Message of the last error on this ctx ("" if none).  Never NULL. */
+const char *wisv_last_error(const wisv_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WISV_H */

@@ -149,8 +149,8 @@ void orc_attend(const float *q, const float *kc, const float *vc, int n_vis, int
     }
 }
 
-/* index of the largest entry (lowest index among equals) and its lead over the runner-up */
-void orc_argmax(const float *z, int n, int32_t *idx, float *gap) {
+/* index of the largest entry (lowest index among equals), its lead over the runner-up, its value */
+void orc_argmax(const float *z, int n, int32_t *idx, float *gap, float *top) {
     int best = 0;
     for (int i = 1; i < n; ++i)
         if (z[i] > z[best]) best = i;
@@ -159,6 +159,7 @@ void orc_argmax(const float *z, int n, int32_t *idx, float *gap) {
         if (i != best && z[i] > second) second = z[i];
     *idx = best;
     *gap = (n > 1) ? z[best] - second : INFINITY;
+    if (top) *top = z[best];
 }
 
 static inline double silu(double x) { return x / (1.0 + exp(-x)); }
@@ -170,13 +171,13 @@ static inline double silu(double x) { return x / (1.0 + exp(-x)); }
  *   cache   float [n_layers][2][n_kv_heads][l_max][head_dim]; rows L..L+K-1 are written
  *   h_t     [K][d_model]  post-final-norm hidden state of each row (float, never rounded)
  *   logits  [K][vocab] or NULL
- *   amax    [K] argmax of each row's logits;  gap [K] top1 - top2
+ *   amax    [K] argmax of each row's logits;  gap [K] top1 - top2;  top1 [K] the largest logit (or NULL)
  * Row j's logits predict the token after draft j.
  * Returns 0, or -1 on a bad argument / allocation failure.
  */
 int orc_forward_block(const orc_model *m, const orc_weights *w, float *cache, int l_max, int L,
                       const int32_t *tokens, int K, float *h_t, float *logits, int32_t *amax,
-                      float *gap) {
+                      float *gap, float *top1) {
     const int d = m->d_model, H = m->n_heads, G = m->n_kv_heads, hd = m->head_dim, F = m->d_ff;
     const int st = m->storage, dq = H * hd, dkv = G * hd, rep = H / G;
     if (K <= 0 || L < 0 || L + K > l_max || H % G) return -1;
@@ -254,7 +255,7 @@ int orc_forward_block(const orc_model *m, const orc_weights *w, float *cache, in
         for (int i = 0; i < d; ++i) a[j * d + i] = maybe_round(m, h_t[j * d + i]);
     }
     orc_linear(a, w->lm_head, st, K, d, m->vocab, zrow);
-    for (int j = 0; j < K; ++j) orc_argmax(zrow + (size_t)j * m->vocab, m->vocab, &amax[j], &gap[j]);
+    for (int j = 0; j < K; ++j) orc_argmax(zrow + (size_t)j * m->vocab, m->vocab, &amax[j], &gap[j], top1 ? &top1[j] : NULL);
     if (logits) memcpy(logits, zrow, sizeof(float) * (size_t)K * m->vocab);
 
     free(x); free(a); free(q); free(kk); free(vv); free(o); free(upd); free(g); free(u); free(zrow);
@@ -334,19 +335,21 @@ void orc_decide(int K, const int32_t *draft, const int32_t *t, const int32_t *sc
  *   pred_next  target argmax for the first draft position (state left by the previous forward)
  *   hd         [n_hd][d_draft] float; hd_row[K] row of hd per position or -1 (not uploaded)
  *   proto      0 full-hidden, 1 selective-hidden: under SH only mismatch positions are scored
- * Outputs: A, y_star, p_acc[K] (1.0 where not scored), t[K+1], gap[K] (logit lead of rows 0..K-1),
+ * Outputs: A, y_star, p_acc[K] (1.0 where not scored), t[K+1], gap[K] / top1[K] (lead and value of the
+ *          largest logit of rows 0..K-1),
  *          mask, status, h_t[K][d_model], p_rej[K] (0.0 where not scored).
  */
 int orc_verify_round(const orc_model *m, const orc_weights *w, float *cache, int l_max, int L,
                      int32_t pred_next, const int32_t *draft, int K, int proto, const float *hd,
                      const int32_t *hd_row, const float *csi, float tau, int gate_all,
                      int32_t *A, int32_t *y_star, float *p_acc, float *p_rej, int32_t *t,
-                     float *gap, uint32_t *mask, uint32_t *status, float *h_t, float *logits) {
+                     float *gap, float *top1, uint32_t *mask, uint32_t *status, float *h_t,
+                     float *logits) {
     if (K > 31) return -1;
     int32_t *amax = malloc(sizeof(int32_t) * K);
     int32_t *scored = malloc(sizeof(int32_t) * K);
     if (!amax || !scored) return -1;
-    int rc = orc_forward_block(m, w, cache, l_max, L, draft, K, h_t, logits, amax, gap);
+    int rc = orc_forward_block(m, w, cache, l_max, L, draft, K, h_t, logits, amax, gap, top1);
     if (rc) { free(amax); free(scored); return rc; }
     t[0] = pred_next;
     for (int j = 0; j < K; ++j) t[j + 1] = amax[j];

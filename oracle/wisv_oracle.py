@@ -120,7 +120,7 @@ def attend(q, k, v) -> np.ndarray:
 def argmax(z):
     z = _f32(z)
     idx, gap = C.c_int32(), C.c_float()
-    lib().orc_argmax(_fp(z), C.c_int(z.size), C.byref(idx), C.byref(gap))
+    lib().orc_argmax(_fp(z), C.c_int(z.size), C.byref(idx), C.byref(gap), None)
     return idx.value, gap.value
 
 
@@ -186,13 +186,14 @@ class Oracle:
         logits = np.empty((k, s.vocab), dtype=np.float32) if want_logits else None
         amax = np.empty(k, dtype=np.int32)
         gap = np.empty(k, dtype=np.float32)
+        top1 = np.empty(k, dtype=np.float32)
         assert cache.dtype == np.float32 and cache.flags.c_contiguous
         rc = lib().orc_forward_block(C.byref(self.m), C.byref(self.w), _fp(cache), cache.shape[3], L,
                                      _fp(tokens), k, _fp(h_t), _fp(logits) if want_logits else None,
-                                     _fp(amax), _fp(gap))
+                                     _fp(amax), _fp(gap), _fp(top1))
         if rc:
             raise ValueError("orc_forward_block rejected its arguments")
-        return {"h_t": h_t, "logits": logits, "argmax": amax, "gap": gap}
+        return {"h_t": h_t, "logits": logits, "argmax": amax, "gap": gap, "top1": top1}
 
     def prefill(self, cache: np.ndarray, tokens, chunk: int = 0) -> int:
         """Fill the cache from position 0 and return the argmax after the last token."""
@@ -224,6 +225,7 @@ class Oracle:
         out = {
             "p_accept": np.empty(k, dtype=np.float32), "p_reject": np.empty(k, dtype=np.float32),
             "t": np.empty(k + 1, dtype=np.int32), "gap": np.empty(k, dtype=np.float32),
+            "top1": np.empty(k, dtype=np.float32),
             "h_t": np.empty((k, s.d_model), dtype=np.float32),
             "logits": np.empty((k, s.vocab), dtype=np.float32) if want_logits else None,
         }
@@ -233,7 +235,7 @@ class Oracle:
             C.byref(self.m), C.byref(self.w), _fp(cache), cache.shape[3], L, int(pred_next),
             _fp(draft), k, int(proto), _fp(hd) if hd.size else None, _fp(hd_row), _fp(csi),
             C.c_float(tau), int(gate_all), C.byref(a), C.byref(y), _fp(out["p_accept"]),
-            _fp(out["p_reject"]), _fp(out["t"]), _fp(out["gap"]), C.byref(mask), C.byref(status),
+            _fp(out["p_reject"]), _fp(out["t"]), _fp(out["gap"]), _fp(out["top1"]), C.byref(mask), C.byref(status),
             _fp(out["h_t"]), _fp(out["logits"]) if want_logits else None)
         if rc:
             raise ValueError("orc_verify_round rejected its arguments")

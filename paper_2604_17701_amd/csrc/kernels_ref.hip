@@ -1,0 +1,446 @@
+// Generic kernels of the verify round: one straightforward kernel per step, templated on the
+// storage type (float or bf16) of weights / cache (WT) and of matrix-product operands (AT).
+// They serve the fp32 configuration and are the fallback wherever no specialised bf16 kernel
+// applies (prefill chunks, unusual shapes).
+#include "wisv_internal.h"
+
+namespace wisv {
+
+template <typename T> __device__ __forceinline__ void load8(const T *p, float *out);
+template <> __device__ __forceinline__ void load8<float>(const float *p, float *out) {
+    float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t *p, float *out) {
+    uint4 a = *reinterpret_cast<const uint4 *>(p);
+    uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(w[i] << 16);
+        out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
+// float sum over a block of NT threads (NT multiple of 64); every thread gets the result
+template <int NT> __device__ __forceinline__ float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) t += red[w];
+    return t;
+}
+template <int NT> __device__ __forceinline__ float block_max(float v, float *red) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = red[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) t = fmaxf(t, red[w]);
+    return t;
+}
+
+// ------------------------------------------------------------------------------------------ rows
+// row m = (stream b = m / k, position j = m % k): slot and absolute position L_b + j
+__global__ void k_prep_rows(const int32_t *__restrict__ stream_ids, const int32_t *__restrict__ kv_len, int k,
+                            int rows, int max_batch, int max_ctx, int32_t *row_slot, int32_t *row_pos) {
+    int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= rows) return;
+    int b = m / k, j = m - b * k;
+    int s = min(max(stream_ids[b], 0), max_batch - 1);
+    row_slot[m] = s;
+    row_pos[m] = min(max(kv_len[s], 0) + j, max_ctx - 1);
+}
+
+void launch_prep_rows(Ctx *c, const Fwd &f) {
+    ProfScope ps(c, KC_PREP);
+    hipLaunchKernelGGL(k_prep_rows, dim3((f.rows + 63) / 64), dim3(64), 0, c->stream, f.stream_ids, c->d_kv_len, f.k,
+                       f.rows, c->cfg.max_batch, c->cfg.max_ctx, c->row_slot, c->row_pos);
+}
+
+// ------------------------------------------------------------------------------------------ embedding
+template <typename WT>
+__global__ void k_embed(const WT *__restrict__ E, const int32_t *__restrict__ tok, int d, int vocab, float *x) {
+    int m = blockIdx.x;
+    int t = min(max(tok[m], 0), vocab - 1);
+    for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = Elem<WT>::load(E + (size_t)t * d + i);
+}
+
+void launch_embed(Ctx *c, const Fwd &f) {
+    ProfScope ps(c, KC_EMBED);
+    if (c->bf16)
+        hipLaunchKernelGGL(k_embed<bf16_t>, dim3(f.rows), dim3(256), 0, c->stream, (const bf16_t *)c->embed, f.tokens,
+                           c->cfg.d_model, c->cfg.vocab, c->x);
+    else
+        hipLaunchKernelGGL(k_embed<float>, dim3(f.rows), dim3(256), 0, c->stream, (const float *)c->embed, f.tokens,
+                           c->cfg.d_model, c->cfg.vocab, c->x);
+}
+
+// ------------------------------------------------------------------------------------------ RMSNorm
+// x[m] += y[0][m] + ... + y[n_partial-1][m] (fixed order), then out[m] = x[m] / sqrt(mean(x^2)+eps) * g
+template <typename WT, typename AT>
+__global__ void k_rmsnorm(float *x, const float *__restrict__ y, int n_partial, size_t partial_stride,
+                          const WT *__restrict__ g, int d, float eps, AT *out, float *out_f32) {
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    float *xr = x + (size_t)m * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = xr[i];
+        for (int p = 0; p < n_partial; ++p) v += y[p * partial_stride + (size_t)m * d + i];
+        if (n_partial) xr[i] = v;
+        ss += v * v;
+    }
+    ss = block_sum<256>(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = xr[i] * inv * Elem<WT>::load(g + i);
+        Elem<AT>::store(out + (size_t)m * d + i, v);
+        if (out_f32) out_f32[(size_t)m * d + i] = v;
+    }
+}
+
+void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, void *out, float *out_f32) {
+    ProfScope ps(c, KC_NORM);
+    const int d = c->cfg.d_model;
+    const size_t stride = (size_t)c->rows_max * d;
+    if (c->bf16)
+        hipLaunchKernelGGL((k_rmsnorm<bf16_t, bf16_t>), dim3(rows), dim3(256), 0, c->stream, c->x, c->y, n_partial,
+                           stride, (const bf16_t *)g, d, c->cfg.rms_eps, (bf16_t *)out, out_f32);
+    else
+        hipLaunchKernelGGL((k_rmsnorm<float, float>), dim3(rows), dim3(256), 0, c->stream, c->x, c->y, n_partial,
+                           stride, (const float *)g, d, c->cfg.rms_eps, (float *)out, out_f32);
+}
+
+// ------------------------------------------------------------------------------------------ GEMM (fallback)
+// Y[r, o] = sum_i A[r, i] W[o, i]; one wave per output feature, MT rows per pass, kd % 8 == 0
+template <typename WT, typename AT, int MT>
+__global__ void k_gemm_ref(const AT *__restrict__ A, const WT *__restrict__ W, float *__restrict__ Y, int rows, int n,
+                           int kd) {
+    const int lane = threadIdx.x & 63, o = blockIdx.x * 4 + (threadIdx.x >> 6), r0 = blockIdx.y * MT;
+    if (o >= n) return;
+    float acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = 0.f;
+    const WT *wr = W + (size_t)o * kd;
+    for (int i = lane * 8; i < kd; i += 512) {
+        float wv[8], av[8];
+        load8<WT>(wr + i, wv);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            if (r0 + t < rows) {
+                load8<AT>(A + (size_t)(r0 + t) * kd + i, av);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[t] = fmaf(av[e], wv[e], acc[t]);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        float s = wave_sum(acc[t]);
+        if (lane == 0 && r0 + t < rows) Y[(size_t)(r0 + t) * n + o] = s;
+    }
+}
+
+void launch_gemm_ref(Ctx *c, const void *A, const void *W, float *Y, int rows, int n, int kd, int kclass) {
+    ProfScope ps(c, kclass);
+    constexpr int MT = 8;
+    dim3 grid((n + 3) / 4, (rows + MT - 1) / MT);
+    if (c->bf16)
+        hipLaunchKernelGGL((k_gemm_ref<bf16_t, bf16_t, MT>), grid, dim3(256), 0, c->stream, (const bf16_t *)A,
+                           (const bf16_t *)W, Y, rows, n, kd);
+    else
+        hipLaunchKernelGGL((k_gemm_ref<float, float, MT>), grid, dim3(256), 0, c->stream, (const float *)A,
+                           (const float *)W, Y, rows, n, kd);
+}
+
+// ------------------------------------------------------------------------------------------ RoPE + KV append
+// grid (rows, H + 2G), block hd/2.  q heads: rotate -> q operand; k heads: rotate -> cache; v heads: copy -> cache
+template <typename WT, typename AT>
+__global__ void k_rope_append(const float *__restrict__ qkv, int H, int G, int hd, const int32_t *__restrict__ row_slot,
+                              const int32_t *__restrict__ row_pos, const float *__restrict__ cs,
+                              const float *__restrict__ sn, AT *q_out, WT *kv_layer, size_t slot_stride, int max_ctx) {
+    const int m = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = hd >> 1;
+    const int d_q = H * hd, d_kv = G * hd, pos = row_pos[m];
+    const float *src = qkv + (size_t)m * (d_q + 2 * d_kv) + (size_t)hh * hd;
+    const float a = src[i], b = src[i + half];
+    const float co = cs[(size_t)pos * half + i], si = sn[(size_t)pos * half + i];
+    if (hh < H) {
+        AT *dst = q_out + (size_t)m * d_q + (size_t)hh * hd;
+        Elem<AT>::store(dst + i, a * co - b * si);
+        Elem<AT>::store(dst + i + half, b * co + a * si);
+    } else if (hh < H + G) {
+        WT *dst = kv_layer + (size_t)row_slot[m] * slot_stride + ((size_t)(hh - H) * max_ctx + pos) * hd;
+        Elem<WT>::store(dst + i, a * co - b * si);
+        Elem<WT>::store(dst + i + half, b * co + a * si);
+    } else {
+        WT *dst = kv_layer + (size_t)row_slot[m] * slot_stride + (size_t)G * max_ctx * hd +
+                  ((size_t)(hh - H - G) * max_ctx + pos) * hd;
+        Elem<WT>::store(dst + i, a);
+        Elem<WT>::store(dst + i + half, b);
+    }
+}
+
+void launch_rope_append(Ctx *c, const Fwd &f, int layer) {
+    ProfScope ps(c, KC_ROPE);
+    const wisv_config &g = c->cfg;
+    const size_t slot_stride = (size_t)2 * g.n_kv_heads * g.max_ctx * g.head_dim;
+    dim3 grid(f.rows, g.n_heads + 2 * g.n_kv_heads), block(g.head_dim / 2);
+    void *kvl = kv_ptr(c, layer, 0, 0);
+    if (c->bf16)
+        hipLaunchKernelGGL((k_rope_append<bf16_t, bf16_t>), grid, block, 0, c->stream, c->qkv, g.n_heads, g.n_kv_heads,
+                           g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, (bf16_t *)c->q, (bf16_t *)kvl,
+                           slot_stride, g.max_ctx);
+    else
+        hipLaunchKernelGGL((k_rope_append<float, float>), grid, block, 0, c->stream, c->qkv, g.n_heads, g.n_kv_heads,
+                           g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, (float *)c->q, (float *)kvl,
+                           slot_stride, g.max_ctx);
+}
+
+// ------------------------------------------------------------------------------------------ attention (fallback)
+// one block per (row, query head): scores of the visible keys in LDS, float softmax, then P.V
+template <typename WT, typename AT>
+__global__ void k_attn_ref(const AT *__restrict__ q, const WT *__restrict__ kv_layer, size_t slot_stride, int H, int G,
+                           int hd, int max_ctx, const int32_t *__restrict__ row_slot,
+                           const int32_t *__restrict__ row_pos, AT *o) {
+    extern __shared__ float smem[];
+    float *qs = smem;            // [hd]
+    float *red = smem + hd;      // [256 + 4]
+    float *sc = red + 260;       // [n_vis]
+    const int m = blockIdx.x, h = blockIdx.y, g = h / (H / G), tid = threadIdx.x;
+    const int n_vis = row_pos[m] + 1;
+    const WT *kc = kv_layer + (size_t)row_slot[m] * slot_stride + (size_t)g * max_ctx * hd;
+    const WT *vc = kc + (size_t)G * max_ctx * hd;
+    if (tid < hd) qs[tid] = Elem<AT>::load(q + (size_t)m * H * hd + (size_t)h * hd + tid);
+    __syncthreads();
+    const float scale = 1.0f / sqrtf((float)hd);
+    float mx = -INFINITY;
+    for (int s = tid; s < n_vis; s += 256) {
+        float acc = 0.f, kvv[8];
+        for (int i = 0; i < hd; i += 8) {
+            load8<WT>(kc + (size_t)s * hd + i, kvv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fmaf(qs[i + e], kvv[e], acc);
+        }
+        acc *= scale;
+        sc[s] = acc;
+        mx = fmaxf(mx, acc);
+    }
+    mx = block_max<256>(mx, red + 256);
+    float sum = 0.f;
+    for (int s = tid; s < n_vis; s += 256) {
+        float e = expf(sc[s] - mx);
+        sc[s] = e;
+        sum += e;
+    }
+    sum = block_sum<256>(sum, red + 256);   // also makes every sc[] visible
+    const int dim = tid % hd, part = tid / hd, nparts = 256 / hd;
+    float acc = 0.f;
+    for (int s = part; s < n_vis; s += nparts) acc = fmaf(sc[s], Elem<WT>::load(vc + (size_t)s * hd + dim), acc);
+    red[tid] = acc;
+    __syncthreads();
+    if (part == 0) {
+        for (int p = 1; p < nparts; ++p) acc += red[p * hd + dim];
+        Elem<AT>::store(o + (size_t)m * H * hd + (size_t)h * hd + dim, acc / sum);
+    }
+}
+
+void launch_attn_ref(Ctx *c, const Fwd &f, int layer) {
+    ProfScope ps(c, KC_ATTN);
+    const wisv_config &g = c->cfg;
+    const size_t slot_stride = (size_t)2 * g.n_kv_heads * g.max_ctx * g.head_dim;
+    const size_t lds = sizeof(float) * (g.head_dim + 260 + f.max_len_ub);
+    dim3 grid(f.rows, g.n_heads);
+    void *kvl = kv_ptr(c, layer, 0, 0);
+    if (c->bf16)
+        hipLaunchKernelGGL((k_attn_ref<bf16_t, bf16_t>), grid, dim3(256), lds, c->stream, (const bf16_t *)c->q,
+                           (const bf16_t *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, g.max_ctx,
+                           c->row_slot, c->row_pos, (bf16_t *)c->o);
+    else
+        hipLaunchKernelGGL((k_attn_ref<float, float>), grid, dim3(256), lds, c->stream, (const float *)c->q,
+                           (const float *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, g.max_ctx, c->row_slot,
+                           c->row_pos, (float *)c->o);
+}
+
+// ------------------------------------------------------------------------------------------ SwiGLU
+template <typename AT> __global__ void k_swiglu(const float *__restrict__ gu, int F, AT *h) {
+    const int m = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= F) return;
+    const float g = gu[(size_t)m * 2 * F + i], u = gu[(size_t)m * 2 * F + F + i];
+    Elem<AT>::store(h + (size_t)m * F + i, g / (1.0f + expf(-g)) * u);
+}
+
+void launch_swiglu(Ctx *c, int rows) {
+    ProfScope ps(c, KC_SWIGLU);
+    const int F = c->cfg.d_ff;
+    dim3 grid((F + 255) / 256, rows);
+    if (c->bf16)
+        hipLaunchKernelGGL(k_swiglu<bf16_t>, grid, dim3(256), 0, c->stream, c->gu, F, (bf16_t *)c->h);
+    else
+        hipLaunchKernelGGL(k_swiglu<float>, grid, dim3(256), 0, c->stream, c->gu, F, (float *)c->h);
+}
+
+// ------------------------------------------------------------------------------------------ argmax over logits rows
+__global__ void k_argmax_rows(const float *__restrict__ z, int V, int32_t *amax) {
+    __shared__ float bv[4];
+    __shared__ int bi[4];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const float *zr = z + (size_t)m * V;
+    float best = -INFINITY;
+    int idx = 0x7fffffff;
+    for (int i = tid; i < V; i += 256) {
+        float v = zr[i];
+        if (v > best || idx == 0x7fffffff) { best = v; idx = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(best, o, 64);
+        int oi = __shfl_xor(idx, o, 64);
+        if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+    }
+    if ((tid & 63) == 0) { bv[tid >> 6] = best; bi[tid >> 6] = idx; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
+        amax[m] = idx == 0x7fffffff ? 0 : idx;
+    }
+}
+
+void launch_argmax(Ctx *c, int rows) {
+    ProfScope ps(c, KC_ARGMAX);
+    hipLaunchKernelGGL(k_argmax_rows, dim3(rows), dim3(256), 0, c->stream, c->logits, c->cfg.vocab, c->amax);
+}
+
+// ------------------------------------------------------------------------------------------ decision head
+// One block per drafted position.  z = [h^D ; h^T ; c] is never built: W1's row is walked in three
+// segments.  h^T and c are float; h^D and the head parameters have the storage type.
+template <typename WT>
+__global__ void k_head(const WT *__restrict__ w1, const WT *__restrict__ b1, const WT *__restrict__ w2,
+                       const WT *__restrict__ b2, int dD, int dT, int dC, int dJ, int act, const WT *__restrict__ hd,
+                       const int32_t *__restrict__ hd_row, int n_hd, const float *__restrict__ h_t,
+                       const float *__restrict__ csi, const int32_t *__restrict__ stream_ids,
+                       const int32_t *__restrict__ proto, const int32_t *__restrict__ tokens,
+                       const int32_t *__restrict__ amax, const int32_t *__restrict__ pred_next, int k, int max_batch,
+                       int gate_all, float *p_acc, int32_t *scored) {
+    __shared__ float red[4];
+    const int m = blockIdx.x, b = m / k, j = m - b * k, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slot = min(max(stream_ids[b], 0), max_batch - 1);
+    const int t_pred = j == 0 ? pred_next[slot] : amax[m - 1];
+    const bool mismatch = tokens[m] != t_pred;
+    int hr = hd_row ? hd_row[m] : m;
+    if (hr >= n_hd) hr = -1;
+    const bool want = gate_all || proto[b] == WISV_PROTO_FH || mismatch;
+    if (!(want && hr >= 0)) {
+        if (tid == 0) { p_acc[m] = 1.0f; scored[m] = 0; }
+        return;
+    }
+    const int din = dD + dT + dC;
+    const WT *hdr = hd + (size_t)hr * dD;
+    const float *htr = h_t + (size_t)m * dT, *cr = csi + (size_t)b * dC;
+    float part = 0.f;
+    for (int r = wave; r < dJ; r += 4) {
+        const WT *wr = w1 + (size_t)r * din;
+        float acc = 0.f;
+        for (int i = lane; i < dD; i += 64) acc = fmaf(Elem<WT>::load(wr + i), Elem<WT>::load(hdr + i), acc);
+        for (int i = lane; i < dT; i += 64) acc = fmaf(Elem<WT>::load(wr + dD + i), htr[i], acc);
+        for (int i = lane; i < dC; i += 64) acc = fmaf(Elem<WT>::load(wr + dD + dT + i), cr[i], acc);
+        acc = wave_sum(acc) + Elem<WT>::load(b1 + r);
+        const float a = act == WISV_ACT_RELU ? fmaxf(acc, 0.f) : acc / (1.0f + expf(-acc));
+        part = fmaf(Elem<WT>::load(w2 + r), a, part);
+    }
+    if (lane == 0) red[wave] = part;
+    __syncthreads();
+    if (tid == 0) {
+        const float s = ((red[0] + red[1]) + (red[2] + red[3])) + Elem<WT>::load(b2);
+        p_acc[m] = 1.0f / (1.0f + expf(s));
+        scored[m] = 1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ localize + first reject
+// one thread per stream
+__global__ void k_decide(int batch, int k, int max_batch, const int32_t *__restrict__ stream_ids,
+                         const int32_t *__restrict__ tokens, const int32_t *__restrict__ amax,
+                         const float *__restrict__ p_acc, const int32_t *__restrict__ scored,
+                         const float *__restrict__ tau, int gate_all, int commit, int32_t *kv_len, int32_t *pred_next,
+                         int32_t *alen, int32_t *ytok, int32_t *targ, uint32_t *mask_out, uint32_t *status_out) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    const int slot = min(max(stream_ids[b], 0), max_batch - 1);
+    const int pn = pred_next[slot];
+    uint32_t mask = 0, status = 0;
+    int first = k;
+    for (int j = k - 1; j >= 0; --j) {
+        const int m = b * k + j;
+        const int t = j == 0 ? pn : amax[m - 1];
+        const bool mismatch = tokens[m] != t;
+        if (mismatch) mask |= 1u << j;
+        if (gate_all || mismatch) {
+            bool reject;
+            if (!scored[m]) { reject = true; status |= WISV_STATUS_MISSING_HIDDEN; }
+            else reject = !(p_acc[m] >= tau[b]);
+            if (reject) first = j;
+        }
+    }
+    const int y = first == 0 ? pn : amax[b * k + first - 1];
+    alen[b] = first;
+    ytok[b] = y;
+    if (targ) {
+        targ[b * (k + 1)] = pn;
+        for (int j = 0; j < k; ++j) targ[b * (k + 1) + j + 1] = amax[b * k + j];
+    }
+    if (mask_out) mask_out[b] = mask;
+    if (status_out) status_out[b] = status;
+    if (commit) {
+        kv_len[slot] += first;
+        pred_next[slot] = y;
+    }
+}
+
+void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in, const wisv_round_out &out) {
+    const wisv_config &g = c->cfg;
+    const int gate_all = (in.flags & WISV_FLAG_GATE_ALL) ? 1 : 0, commit = (in.flags & WISV_FLAG_NO_COMMIT) ? 0 : 1;
+    int32_t *scored = c->scored;
+    {
+        ProfScope ps(c, KC_HEAD);
+        if (c->bf16)
+            hipLaunchKernelGGL(k_head<bf16_t>, dim3(f.rows), dim3(256), 0, c->stream, (const bf16_t *)c->head_w1,
+                               (const bf16_t *)c->head_b1, (const bf16_t *)c->head_w2, (const bf16_t *)c->head_b2,
+                               g.d_draft, g.d_model, g.d_csi, g.d_head_hidden, g.head_act, (const bf16_t *)in.hd,
+                               in.hd_row, in.n_hd, c->h_t, in.csi, in.stream_ids, in.proto, in.draft_tokens, c->amax,
+                               c->d_pred_next, f.k, g.max_batch, gate_all, out.p_accept, scored);
+        else
+            hipLaunchKernelGGL(k_head<float>, dim3(f.rows), dim3(256), 0, c->stream, (const float *)c->head_w1,
+                               (const float *)c->head_b1, (const float *)c->head_w2, (const float *)c->head_b2,
+                               g.d_draft, g.d_model, g.d_csi, g.d_head_hidden, g.head_act, (const float *)in.hd,
+                               in.hd_row, in.n_hd, c->h_t, in.csi, in.stream_ids, in.proto, in.draft_tokens, c->amax,
+                               c->d_pred_next, f.k, g.max_batch, gate_all, out.p_accept, scored);
+    }
+    {
+        ProfScope ps(c, KC_DECIDE);
+        hipLaunchKernelGGL(k_decide, dim3((f.batch + 63) / 64), dim3(64), 0, c->stream, f.batch, f.k, g.max_batch,
+                           in.stream_ids, in.draft_tokens, c->amax, out.p_accept, scored, in.tau, gate_all, commit,
+                           c->d_kv_len, c->d_pred_next, out.accepted_len, out.correction_token, out.target_argmax,
+                           out.mismatch_mask, out.status);
+    }
+}
+
+// after a prefill chunk: the slot's length grows by the chunk, pred_next = greedy token of its last row
+__global__ void k_set_pred_next(int32_t *kv_len, int32_t *pred_next, const int32_t *amax, int slot, int row,
+                                int new_len) {
+    pred_next[slot] = amax[row];
+    kv_len[slot] = new_len;
+}
+
+void launch_set_pred_next(Ctx *c, int slot, int row, int new_len) {
+    hipLaunchKernelGGL(k_set_pred_next, dim3(1), dim3(1), 0, c->stream, c->d_kv_len, c->d_pred_next, c->amax, slot, row,
+                       new_len);
+}
+
+}  // namespace wisv

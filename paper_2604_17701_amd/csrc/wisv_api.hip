@@ -1,0 +1,623 @@
+// C ABI of the WISV verify round: context management, argument checking and the order in which
+// the kernels of one round are enqueued (Alg. 1: Verify -> Localize -> head -> first reject).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "wisv_internal.h"
+
+using namespace wisv;
+
+struct wisv_ctx : public wisv::Ctx {};
+
+namespace wisv {
+
+void *kv_ptr(const Ctx *c, int layer, int slot, int which) {
+    const wisv_config &g = c->cfg;
+    const size_t half = (size_t)g.n_kv_heads * g.max_ctx * g.head_dim;
+    const size_t off = (((size_t)layer * g.max_batch + slot) * 2 + which) * half;
+    return (char *)c->kv + off * c->esz;
+}
+
+ProfScope::ProfScope(Ctx *c_, int kclass) : c(c_), idx(-1) {
+    if (!c->profiling) return;
+    if (c->ev_used + 2 > c->ev_pool.size()) {
+        for (int i = 0; i < 2; ++i) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            c->ev_pool.push_back(e);
+        }
+    }
+    idx = (int)c->ev_used;
+    c->ev_used += 2;
+    c->ev_class.resize(c->ev_used / 2);
+    c->ev_class[idx / 2] = kclass;
+    (void)hipEventRecord(c->ev_pool[idx], c->stream);
+}
+ProfScope::~ProfScope() {
+    if (idx >= 0) (void)hipEventRecord(c->ev_pool[idx + 1], c->stream);
+}
+
+}  // namespace wisv
+
+// ------------------------------------------------------------------------------------------ helpers
+
+static int fail(Ctx *c, int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    return code;
+}
+
+#define HIP_TRY(c, call)                                                                                   \
+    do {                                                                                                   \
+        hipError_t e_ = (call);                                                                            \
+        if (e_ != hipSuccess) return fail((c), WISV_EHIP, "%s: %s", #call, hipGetErrorString(e_));         \
+    } while (0)
+
+static const char *check_config(const wisv_config *g) {
+    if (!g) return "config is NULL";
+    if (g->n_layers < 1 || g->n_layers > 1024) return "n_layers out of range";
+    if (g->d_model < 8 || g->d_model % 8) return "d_model must be a positive multiple of 8";
+    if (g->n_heads < 1 || g->n_kv_heads < 1 || g->n_heads % g->n_kv_heads) return "n_heads must be a multiple of n_kv_heads";
+    if (g->head_dim != 32 && g->head_dim != 64 && g->head_dim != 128 && g->head_dim != 256)
+        return "head_dim must be 32, 64, 128 or 256";
+    if (g->d_ff < 8 || g->d_ff % 8) return "d_ff must be a positive multiple of 8";
+    if (g->vocab < 2) return "vocab must be at least 2";
+    if (!(g->rms_eps > 0.f) || !(g->rope_theta > 1.f)) return "rms_eps must be > 0 and rope_theta > 1";
+    if (g->dtype != WISV_F32 && g->dtype != WISV_BF16) return "dtype must be WISV_F32 or WISV_BF16";
+    if (g->d_draft < 1 || g->d_csi < 1 || g->d_csi > 16 || g->d_head_hidden < 1) return "decision-head sizes out of range";
+    if (g->head_act != WISV_ACT_SILU && g->head_act != WISV_ACT_RELU) return "head_act must be SiLU or ReLU";
+    if (g->max_batch < 1 || g->max_batch > 4096) return "max_batch out of range";
+    if (g->max_k < 1 || g->max_k > WISV_MAX_K) return "max_k out of range";
+    if (g->max_ctx <= g->max_k || g->max_ctx > (1 << 20)) return "max_ctx must exceed max_k (and be at most 2^20)";
+    if (g->device_id < 0) return "device_id is negative";
+    const size_t esz = g->dtype == WISV_BF16 ? 2 : 4;
+    const size_t need = (size_t)g->n_layers * g->max_batch * 2 * g->n_kv_heads * g->max_ctx * g->head_dim * esz;
+    if (g->kv_cache && g->kv_bytes < need) return "borrowed kv_cache is smaller than the cache layout";
+    return nullptr;
+}
+
+static const char *check_weights(const wisv_config *g, const wisv_weights *w) {
+    if (!w) return "weights is NULL";
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->head_w1 || !w->head_b1 || !w->head_w2 || !w->head_b2)
+        return "a weight pointer is NULL";
+    if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+        return "a per-layer pointer array is NULL";
+    for (int l = 0; l < g->n_layers; ++l)
+        if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate[l] ||
+            !w->w_up[l] || !w->w_down[l])
+            return "a per-layer weight pointer is NULL";
+    return nullptr;
+}
+
+template <typename T> static hipError_t dalloc(Ctx *c, T **p, size_t count) {
+    void *q = nullptr;
+    hipError_t e = hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T));
+    if (e == hipSuccess) c->owned.push_back(q);
+    *p = (T *)q;
+    return e;
+}
+
+static void destroy_ctx(Ctx *c) {
+    if (!c) return;
+    (void)hipSetDevice(c->cfg.device_id);
+    (void)hipStreamSynchronize(c->stream);
+    for (void *p : c->owned) (void)hipFree(p);
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    if (c->ev_round[0]) (void)hipEventDestroy(c->ev_round[0]);
+    if (c->ev_round[1]) (void)hipEventDestroy(c->ev_round[1]);
+    delete static_cast<wisv_ctx *>(c);
+}
+
+// ------------------------------------------------------------------------------------------ create / destroy
+
+extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *weights, wisv_ctx **out, char *err,
+                               size_t err_len) {
+    auto report = [&](int code, const std::string &msg) {
+        if (err && err_len) snprintf(err, err_len, "%s", msg.c_str());
+        if (out) *out = nullptr;
+        return code;
+    };
+    if (!out) return report(WISV_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (const char *m = check_config(config)) return report(WISV_EINVAL, m);
+    if (const char *m = check_weights(config, weights)) return report(WISV_EINVAL, m);
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
+        return report(WISV_EHIP, "no HIP device available: this library has no CPU fallback");
+    if (config->device_id >= ndev) return report(WISV_EINVAL, "device_id exceeds the device count");
+
+    wisv_ctx *c = new (std::nothrow) wisv_ctx();
+    if (!c) return report(WISV_ENOMEM, "host allocation failed");
+    c->cfg = *config;
+    c->stream = (hipStream_t)config->hip_stream;
+    c->bf16 = config->dtype == WISV_BF16;
+    c->esz = c->bf16 ? 2 : 4;
+    c->d_q = config->n_heads * config->head_dim;
+    c->d_kv = config->n_kv_heads * config->head_dim;
+    c->d_qkv = c->d_q + 2 * c->d_kv;
+    c->rows_max = config->max_batch * config->max_k;
+    c->profiling = false;
+    c->ev_used = 0;
+    c->ev_round[0] = c->ev_round[1] = nullptr;
+    c->logits = nullptr;
+    c->logits_rows = 0;
+    c->last_rows = 0;
+    memset(c->prof_ms, 0, sizeof c->prof_ms);
+    memset(c->prof_n, 0, sizeof c->prof_n);
+    c->h_len_ub.assign(config->max_batch, 0);
+
+    auto bail = [&](int code, const std::string &msg) {
+        destroy_ctx(c);
+        return report(code, msg);
+    };
+#define CREATE_TRY(call)                                                                        \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return bail(e_ == hipErrorOutOfMemory ? WISV_ENOMEM : WISV_EHIP,                    \
+                        std::string(#call) + ": " + hipGetErrorString(e_));                     \
+    } while (0)
+
+    const wisv_config &g = c->cfg;
+    const size_t esz = c->esz;
+    const int d = g.d_model, F = g.d_ff, V = g.vocab, R = c->rows_max;
+    CREATE_TRY(hipSetDevice(g.device_id));
+    CREATE_TRY(hipEventCreate(&c->ev_round[0]));
+    CREATE_TRY(hipEventCreate(&c->ev_round[1]));
+
+    // ---- parameters: private copies; q/k/v and gate/up are stacked so that one product serves each group
+    auto copy_in = [&](void **dst, const void *src, size_t elems) -> hipError_t {
+        char *p;
+        hipError_t e = dalloc(c, &p, elems * esz);
+        if (e != hipSuccess) return e;
+        *dst = p;
+        return hipMemcpyAsync(p, src, elems * esz, hipMemcpyDeviceToDevice, c->stream);
+    };
+    CREATE_TRY(copy_in(&c->embed, weights->embed, (size_t)V * d));
+    CREATE_TRY(copy_in(&c->lm_head, weights->lm_head, (size_t)V * d));
+    CREATE_TRY(copy_in(&c->final_norm, weights->final_norm, d));
+    CREATE_TRY(copy_in(&c->head_w1, weights->head_w1, (size_t)g.d_head_hidden * (g.d_draft + d + g.d_csi)));
+    CREATE_TRY(copy_in(&c->head_b1, weights->head_b1, g.d_head_hidden));
+    CREATE_TRY(copy_in(&c->head_w2, weights->head_w2, g.d_head_hidden));
+    CREATE_TRY(copy_in(&c->head_b2, weights->head_b2, 1));
+    c->layers.resize(g.n_layers);
+    for (int l = 0; l < g.n_layers; ++l) {
+        LayerW &L = c->layers[l];
+        CREATE_TRY(copy_in(&L.attn_norm, weights->attn_norm[l], d));
+        CREATE_TRY(copy_in(&L.ffn_norm, weights->ffn_norm[l], d));
+        CREATE_TRY(copy_in(&L.wo, weights->wo[l], (size_t)d * c->d_q));
+        CREATE_TRY(copy_in(&L.wdown, weights->w_down[l], (size_t)d * F));
+        char *p;
+        CREATE_TRY(dalloc(c, &p, (size_t)c->d_qkv * d * esz));
+        L.wqkv = p;
+        CREATE_TRY(hipMemcpyAsync(p, weights->wq[l], (size_t)c->d_q * d * esz, hipMemcpyDeviceToDevice, c->stream));
+        CREATE_TRY(hipMemcpyAsync(p + (size_t)c->d_q * d * esz, weights->wk[l], (size_t)c->d_kv * d * esz,
+                                  hipMemcpyDeviceToDevice, c->stream));
+        CREATE_TRY(hipMemcpyAsync(p + (size_t)(c->d_q + c->d_kv) * d * esz, weights->wv[l], (size_t)c->d_kv * d * esz,
+                                  hipMemcpyDeviceToDevice, c->stream));
+        CREATE_TRY(dalloc(c, &p, (size_t)2 * F * d * esz));
+        L.wgu = p;
+        CREATE_TRY(hipMemcpyAsync(p, weights->w_gate[l], (size_t)F * d * esz, hipMemcpyDeviceToDevice, c->stream));
+        CREATE_TRY(hipMemcpyAsync(p + (size_t)F * d * esz, weights->w_up[l], (size_t)F * d * esz,
+                                  hipMemcpyDeviceToDevice, c->stream));
+    }
+
+    // ---- rotary tables, computed in double: angle(pos, i) = pos * theta^(-2i/hd)
+    {
+        const int half = g.head_dim / 2;
+        std::vector<float> hc((size_t)g.max_ctx * half), hs((size_t)g.max_ctx * half);
+        for (int i = 0; i < half; ++i) {
+            const double inv = pow((double)g.rope_theta, -2.0 * i / g.head_dim);
+            for (int p = 0; p < g.max_ctx; ++p) {
+                hc[(size_t)p * half + i] = (float)cos(p * inv);
+                hs[(size_t)p * half + i] = (float)sin(p * inv);
+            }
+        }
+        CREATE_TRY(dalloc(c, &c->rope_cos, hc.size()));
+        CREATE_TRY(dalloc(c, &c->rope_sin, hs.size()));
+        CREATE_TRY(hipMemcpy(c->rope_cos, hc.data(), hc.size() * 4, hipMemcpyHostToDevice));
+        CREATE_TRY(hipMemcpy(c->rope_sin, hs.data(), hs.size() * 4, hipMemcpyHostToDevice));
+    }
+
+    // ---- KV cache and stream state
+    const size_t kv_elems = (size_t)g.n_layers * g.max_batch * 2 * g.n_kv_heads * g.max_ctx * g.head_dim;
+    if (g.kv_cache) {
+        c->kv = g.kv_cache;
+        c->kv_owned = false;
+    } else {
+        char *p;
+        CREATE_TRY(dalloc(c, &p, kv_elems * esz));
+        c->kv = p;
+        c->kv_owned = true;
+        CREATE_TRY(hipMemsetAsync(p, 0, kv_elems * esz, c->stream));
+    }
+    CREATE_TRY(dalloc(c, &c->d_kv_len, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->d_pred_next, g.max_batch));
+    CREATE_TRY(hipMemsetAsync(c->d_kv_len, 0, g.max_batch * 4, c->stream));
+    CREATE_TRY(hipMemsetAsync(c->d_pred_next, 0, g.max_batch * 4, c->stream));
+
+    // ---- staging of a round's inputs / outputs, scratch of the forward
+    CREATE_TRY(dalloc(c, &c->d_stream_ids, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->d_tokens, R));
+    CREATE_TRY(dalloc(c, &c->d_proto, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->d_hd_row, R));
+    {
+        char *p;
+        CREATE_TRY(dalloc(c, &p, (size_t)R * g.d_draft * esz));
+        c->d_hd = p;
+    }
+    CREATE_TRY(dalloc(c, &c->d_csi, (size_t)g.max_batch * g.d_csi));
+    CREATE_TRY(dalloc(c, &c->d_tau, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->d_alen, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->d_ytok, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->d_targ, (size_t)g.max_batch * (g.max_k + 1)));
+    CREATE_TRY(dalloc(c, &c->d_pacc, R));
+    CREATE_TRY(dalloc(c, &c->d_mask, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->d_status, g.max_batch));
+    CREATE_TRY(dalloc(c, &c->row_slot, R));
+    CREATE_TRY(dalloc(c, &c->row_pos, R));
+    CREATE_TRY(dalloc(c, &c->amax, R));
+    CREATE_TRY(dalloc(c, &c->scored, R));
+    CREATE_TRY(dalloc(c, &c->x, (size_t)R * d));
+    CREATE_TRY(dalloc(c, &c->y, (size_t)R * d));
+    CREATE_TRY(dalloc(c, &c->qkv, (size_t)R * c->d_qkv));
+    CREATE_TRY(dalloc(c, &c->gu, (size_t)R * 2 * F));
+    CREATE_TRY(dalloc(c, &c->h_t, (size_t)R * d));
+    {
+        char *p;
+        CREATE_TRY(dalloc(c, &p, (size_t)R * d * esz));
+        c->a = p;
+        CREATE_TRY(dalloc(c, &p, (size_t)R * c->d_q * esz));
+        c->q = p;
+        CREATE_TRY(dalloc(c, &p, (size_t)R * c->d_q * esz));
+        c->o = p;
+        CREATE_TRY(dalloc(c, &p, (size_t)R * F * esz));
+        c->h = p;
+    }
+    CREATE_TRY(dalloc(c, &c->logits, (size_t)R * V));
+    c->logits_rows = R;
+    CREATE_TRY(hipStreamSynchronize(c->stream));
+#undef CREATE_TRY
+    *out = c;
+    if (err && err_len) err[0] = 0;
+    return WISV_OK;
+}
+
+extern "C" int wisv_destroy(wisv_ctx *ctx) {
+    destroy_ctx(ctx);
+    return WISV_OK;
+}
+
+extern "C" const char *wisv_last_error(const wisv_ctx *ctx) { return ctx ? ctx->err.c_str() : ""; }
+
+// ------------------------------------------------------------------------------------------ the target forward
+
+// Enqueues the decoder over f.rows rows (Alg. 1 "Verify"): leaves h^T in c->h_t and the greedy token of
+// every row in c->amax.
+static void enqueue_forward(Ctx *c, const Fwd &f) {
+    const wisv_config &g = c->cfg;
+    const int d = g.d_model, F = g.d_ff;
+    launch_prep_rows(c, f);
+    launch_embed(c, f);
+    for (int l = 0; l < g.n_layers; ++l) {
+        const LayerW &L = c->layers[l];
+        launch_rmsnorm(c, f.rows, l == 0 ? 0 : 1, L.attn_norm, c->a, nullptr);     // + previous FFN update
+        launch_gemm_ref(c, c->a, L.wqkv, c->qkv, f.rows, c->d_qkv, d, KC_GEMM);
+        launch_rope_append(c, f, l);
+        launch_attn_ref(c, f, l);
+        launch_gemm_ref(c, c->o, L.wo, c->y, f.rows, d, c->d_q, KC_GEMM);
+        launch_rmsnorm(c, f.rows, 1, L.ffn_norm, c->a, nullptr);                   // + attention update
+        launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM);
+        launch_swiglu(c, f.rows);
+        launch_gemm_ref(c, c->h, L.wdown, c->y, f.rows, d, F, KC_GEMM);
+    }
+    launch_rmsnorm(c, f.rows, 1, c->final_norm, c->a, c->h_t);
+    launch_gemm_ref(c, c->a, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
+    launch_argmax(c, f.rows);
+}
+
+// ------------------------------------------------------------------------------------------ verify round
+
+static int check_round(Ctx *c, const wisv_round_in *in, const wisv_round_out *out) {
+    if (!in || !out) return fail(c, WISV_EINVAL, "round_in / round_out is NULL");
+    const wisv_config &g = c->cfg;
+    if (in->batch < 1 || in->batch > g.max_batch) return fail(c, WISV_EINVAL, "batch %d outside [1, %d]", in->batch, g.max_batch);
+    if (in->k < 1 || in->k > g.max_k) return fail(c, WISV_EINVAL, "k %d outside [1, max_k = %d]", in->k, g.max_k);
+    if (!in->stream_ids || !in->draft_tokens || !in->proto || !in->csi || !in->tau)
+        return fail(c, WISV_EINVAL, "a required round_in pointer is NULL");
+    if (in->n_hd < 0 || in->n_hd > in->batch * in->k) return fail(c, WISV_EINVAL, "n_hd %d outside [0, batch*k]", in->n_hd);
+    if (in->n_hd > 0 && !in->hd) return fail(c, WISV_EINVAL, "hd is NULL but n_hd > 0");
+    if (!in->hd_row && in->n_hd != in->batch * in->k)
+        return fail(c, WISV_EINVAL, "hd_row is NULL (identity map) but n_hd != batch*k");
+    if (!out->accepted_len || !out->correction_token || !out->p_accept)
+        return fail(c, WISV_EINVAL, "a required round_out pointer is NULL");
+    if (in->flags & ~(WISV_FLAG_GATE_ALL | WISV_FLAG_NO_COMMIT | WISV_FLAG_DEVICE_IO | WISV_FLAG_KEEP_LOGITS))
+        return fail(c, WISV_EINVAL, "unknown flag bits 0x%x", in->flags);
+    return WISV_OK;
+}
+
+extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_round_out *out) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    int rc = check_round(c, in, out);
+    if (rc) return rc;
+    const wisv_config &g = c->cfg;
+    const int B = in->batch, K = in->k, R = B * K;
+    const bool dev_io = in->flags & WISV_FLAG_DEVICE_IO, commit = !(in->flags & WISV_FLAG_NO_COMMIT);
+
+    int len_ub = 0;
+    if (!dev_io) {
+        // host-visible arguments: check their values before anything is enqueued
+        std::vector<char> seen(g.max_batch, 0);
+        for (int b = 0; b < B; ++b) {
+            const int s = in->stream_ids[b];
+            if (s < 0 || s >= g.max_batch) return fail(c, WISV_EINVAL, "stream_ids[%d] = %d outside [0, %d)", b, s, g.max_batch);
+            if (seen[s]) return fail(c, WISV_EINVAL, "stream id %d appears twice", s);
+            seen[s] = 1;
+            if (in->proto[b] != WISV_PROTO_FH && in->proto[b] != WISV_PROTO_SH)
+                return fail(c, WISV_EINVAL, "proto[%d] = %d is neither FH nor SH", b, in->proto[b]);
+            if ((in->flags & WISV_FLAG_GATE_ALL) && in->proto[b] != WISV_PROTO_FH)
+                return fail(c, WISV_EINVAL, "WISV_FLAG_GATE_ALL needs full-hidden upload on every stream");
+            if (c->h_len_ub[s] + K > g.max_ctx)
+                return fail(c, WISV_ESTATE, "stream %d: cached length %d + k %d exceeds max_ctx %d", s, c->h_len_ub[s], K, g.max_ctx);
+            len_ub = std::max(len_ub, c->h_len_ub[s] + K);
+        }
+        for (int m = 0; m < R; ++m) {
+            if (in->draft_tokens[m] < 0 || in->draft_tokens[m] >= g.vocab)
+                return fail(c, WISV_EINVAL, "draft_tokens[%d] = %d outside the vocabulary", m, in->draft_tokens[m]);
+            if (in->hd_row && (in->hd_row[m] < -1 || in->hd_row[m] >= in->n_hd))
+                return fail(c, WISV_EINVAL, "hd_row[%d] = %d outside [-1, n_hd)", m, in->hd_row[m]);
+        }
+    } else {
+        // device-resident arguments cannot be inspected here; kernels clamp ids, tokens and rows
+        for (int s = 0; s < g.max_batch; ++s) len_ub = std::max(len_ub, c->h_len_ub[s] + K);
+        if (len_ub > g.max_ctx)
+            return fail(c, WISV_ESTATE, "a stream may exceed max_ctx; resynchronise with wisv_get_state");
+    }
+
+    HIP_TRY(c, hipSetDevice(g.device_id));
+    wisv_round_in din = *in;
+    wisv_round_out dout = *out;
+    if (!dev_io) {
+        HIP_TRY(c, hipMemcpyAsync(c->d_stream_ids, in->stream_ids, B * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_tokens, in->draft_tokens, R * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_proto, in->proto, B * 4, hipMemcpyHostToDevice, c->stream));
+        if (in->hd_row) HIP_TRY(c, hipMemcpyAsync(c->d_hd_row, in->hd_row, R * 4, hipMemcpyHostToDevice, c->stream));
+        if (in->n_hd)
+            HIP_TRY(c, hipMemcpyAsync(c->d_hd, in->hd, (size_t)in->n_hd * g.d_draft * c->esz, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_csi, in->csi, (size_t)B * g.d_csi * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_tau, in->tau, B * 4, hipMemcpyHostToDevice, c->stream));
+        din.stream_ids = c->d_stream_ids;
+        din.draft_tokens = c->d_tokens;
+        din.proto = c->d_proto;
+        din.hd_row = in->hd_row ? c->d_hd_row : nullptr;
+        din.hd = c->d_hd;
+        din.csi = c->d_csi;
+        din.tau = c->d_tau;
+        dout.accepted_len = c->d_alen;
+        dout.correction_token = c->d_ytok;
+        dout.p_accept = c->d_pacc;
+        dout.target_argmax = c->d_targ;
+        dout.mismatch_mask = c->d_mask;
+        dout.status = c->d_status;
+    }
+
+    Fwd f;
+    f.rows = R;
+    f.batch = B;
+    f.k = K;
+    f.stream_ids = din.stream_ids;
+    f.tokens = din.draft_tokens;
+    f.keep_logits = in->flags & WISV_FLAG_KEEP_LOGITS;
+    f.max_len_ub = len_ub;
+
+    HIP_TRY(c, hipEventRecord(c->ev_round[0], c->stream));
+    enqueue_forward(c, f);
+    launch_head_decide(c, f, din, dout);
+    HIP_TRY(c, hipEventRecord(c->ev_round[1], c->stream));
+    HIP_TRY(c, hipGetLastError());
+    c->last_rows = R;
+
+    if (!dev_io) {
+        std::vector<int32_t> alen(B);
+        HIP_TRY(c, hipMemcpyAsync(alen.data(), c->d_alen, B * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(out->correction_token, c->d_ytok, B * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(out->p_accept, c->d_pacc, R * 4, hipMemcpyDeviceToHost, c->stream));
+        if (out->target_argmax)
+            HIP_TRY(c, hipMemcpyAsync(out->target_argmax, c->d_targ, (size_t)B * (K + 1) * 4, hipMemcpyDeviceToHost, c->stream));
+        if (out->mismatch_mask) HIP_TRY(c, hipMemcpyAsync(out->mismatch_mask, c->d_mask, B * 4, hipMemcpyDeviceToHost, c->stream));
+        if (out->status) HIP_TRY(c, hipMemcpyAsync(out->status, c->d_status, B * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        for (int b = 0; b < B; ++b) {
+            out->accepted_len[b] = alen[b];
+            if (commit) c->h_len_ub[in->stream_ids[b]] += alen[b];
+        }
+    } else if (commit) {
+        for (int s = 0; s < g.max_batch; ++s) c->h_len_ub[s] = std::min(c->h_len_ub[s] + K, g.max_ctx);
+    }
+    return WISV_OK;
+}
+
+// ------------------------------------------------------------------------------------------ state helpers
+
+static int check_slot(Ctx *c, int32_t s) {
+    if (s < 0 || s >= c->cfg.max_batch) return fail(c, WISV_EINVAL, "stream_id %d outside [0, %d)", s, c->cfg.max_batch);
+    return WISV_OK;
+}
+
+extern "C" int wisv_set_state(wisv_ctx *ctx, int32_t stream_id, int32_t kv_len, int32_t pred_next) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (int rc = check_slot(c, stream_id)) return rc;
+    if (kv_len < 0 || kv_len > c->cfg.max_ctx) return fail(c, WISV_EINVAL, "kv_len %d outside [0, max_ctx]", kv_len);
+    if (pred_next < 0 || pred_next >= c->cfg.vocab) return fail(c, WISV_EINVAL, "pred_next %d outside the vocabulary", pred_next);
+    HIP_TRY(c, hipSetDevice(c->cfg.device_id));
+    HIP_TRY(c, hipMemcpyAsync(c->d_kv_len + stream_id, &kv_len, 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_pred_next + stream_id, &pred_next, 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->h_len_ub[stream_id] = kv_len;
+    return WISV_OK;
+}
+
+extern "C" int wisv_get_state(wisv_ctx *ctx, int32_t stream_id, int32_t *kv_len, int32_t *pred_next) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (int rc = check_slot(c, stream_id)) return rc;
+    HIP_TRY(c, hipSetDevice(c->cfg.device_id));
+    int32_t l = 0, p = 0;
+    HIP_TRY(c, hipMemcpyAsync(&l, c->d_kv_len + stream_id, 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(&p, c->d_pred_next + stream_id, 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->h_len_ub[stream_id] = l;
+    if (kv_len) *kv_len = l;
+    if (pred_next) *pred_next = p;
+    return WISV_OK;
+}
+
+extern "C" int wisv_prefill(wisv_ctx *ctx, int32_t stream_id, const int32_t *tokens, int32_t n) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (int rc = check_slot(c, stream_id)) return rc;
+    if (!tokens || n < 1) return fail(c, WISV_EINVAL, "tokens is NULL or n < 1");
+    const wisv_config &g = c->cfg;
+    for (int i = 0; i < n; ++i)
+        if (tokens[i] < 0 || tokens[i] >= g.vocab) return fail(c, WISV_EINVAL, "tokens[%d] outside the vocabulary", i);
+    int32_t len = 0;
+    if (int rc = wisv_get_state(ctx, stream_id, &len, nullptr)) return rc;
+    if (len + n > g.max_ctx) return fail(c, WISV_ESTATE, "prefill of %d tokens at length %d exceeds max_ctx %d", n, len, g.max_ctx);
+    HIP_TRY(c, hipMemcpyAsync(c->d_stream_ids, &stream_id, 4, hipMemcpyHostToDevice, c->stream));
+    const int chunk = c->rows_max;
+    for (int c0 = 0; c0 < n; c0 += chunk) {
+        const int rows = std::min(chunk, n - c0);
+        HIP_TRY(c, hipMemcpyAsync(c->d_tokens, tokens + c0, rows * 4, hipMemcpyHostToDevice, c->stream));
+        Fwd f;
+        f.rows = rows;
+        f.batch = 1;
+        f.k = rows;
+        f.stream_ids = c->d_stream_ids;
+        f.tokens = c->d_tokens;
+        f.keep_logits = false;
+        f.max_len_ub = len + c0 + rows;
+        enqueue_forward(c, f);
+        launch_set_pred_next(c, stream_id, rows - 1, len + c0 + rows);
+        HIP_TRY(c, hipStreamSynchronize(c->stream));   // d_tokens is reused by the next chunk
+    }
+    HIP_TRY(c, hipGetLastError());
+    c->h_len_ub[stream_id] = len + n;
+    return WISV_OK;
+}
+
+static int kv_copy(Ctx *c, int32_t stream_id, int32_t layer, void *host_k, void *host_v, int32_t len, bool to_device) {
+    if (int rc = check_slot(c, stream_id)) return rc;
+    const wisv_config &g = c->cfg;
+    if (layer < 0 || layer >= g.n_layers) return fail(c, WISV_EINVAL, "layer %d outside [0, %d)", layer, g.n_layers);
+    if (len < 0 || len > g.max_ctx) return fail(c, WISV_EINVAL, "len %d outside [0, max_ctx]", len);
+    if (!host_k || !host_v) return fail(c, WISV_EINVAL, "host buffer is NULL");
+    if (len == 0) return WISV_OK;
+    HIP_TRY(c, hipSetDevice(g.device_id));
+    const size_t row = (size_t)g.head_dim * c->esz;
+    for (int which = 0; which < 2; ++which) {
+        char *dev = (char *)kv_ptr(c, layer, stream_id, which);
+        char *host = (char *)(which ? host_v : host_k);
+        // device pitch: max_ctx rows per head; host pitch: len rows per head
+        if (to_device)
+            HIP_TRY(c, hipMemcpy2DAsync(dev, (size_t)g.max_ctx * row, host, (size_t)len * row, (size_t)len * row,
+                                        g.n_kv_heads, hipMemcpyHostToDevice, c->stream));
+        else
+            HIP_TRY(c, hipMemcpy2DAsync(host, (size_t)len * row, dev, (size_t)g.max_ctx * row, (size_t)len * row,
+                                        g.n_kv_heads, hipMemcpyDeviceToHost, c->stream));
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return WISV_OK;
+}
+
+extern "C" int wisv_kv_import(wisv_ctx *ctx, int32_t stream_id, int32_t layer, const void *host_k, const void *host_v,
+                              int32_t len) {
+    if (!ctx) return WISV_EINVAL;
+    return kv_copy(ctx, stream_id, layer, (void *)host_k, (void *)host_v, len, true);
+}
+
+extern "C" int wisv_kv_export(wisv_ctx *ctx, int32_t stream_id, int32_t layer, void *host_k, void *host_v, int32_t len) {
+    if (!ctx) return WISV_EINVAL;
+    return kv_copy(ctx, stream_id, layer, host_k, host_v, len, false);
+}
+
+// ------------------------------------------------------------------------------------------ diagnostics
+
+extern "C" int wisv_debug_copy(wisv_ctx *ctx, int32_t what, void *host_dst, size_t bytes) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (!host_dst) return fail(c, WISV_EINVAL, "host_dst is NULL");
+    const void *src = nullptr;
+    size_t have = 0;
+    if (what == WISV_DBG_HIDDEN) {
+        src = c->h_t;
+        have = (size_t)c->last_rows * c->cfg.d_model * 4;
+    } else if (what == WISV_DBG_LOGITS) {
+        src = c->logits;
+        have = (size_t)c->last_rows * c->cfg.vocab * 4;
+    } else
+        return fail(c, WISV_EINVAL, "unknown debug buffer %d", what);
+    if (bytes > have) return fail(c, WISV_EINVAL, "asked for %zu bytes, the last round left %zu", bytes, have);
+    HIP_TRY(c, hipSetDevice(c->cfg.device_id));
+    HIP_TRY(c, hipMemcpyAsync(host_dst, src, bytes, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return WISV_OK;
+}
+
+extern "C" int wisv_last_round_ms(wisv_ctx *ctx, float *ms) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (!ms) return fail(c, WISV_EINVAL, "ms is NULL");
+    HIP_TRY(c, hipEventSynchronize(c->ev_round[1]));
+    HIP_TRY(c, hipEventElapsedTime(ms, c->ev_round[0], c->ev_round[1]));
+    return WISV_OK;
+}
+
+static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm", "rope_append", "attention",
+                                            "swiglu", "lm_head", "argmax", "head", "decide"};
+
+extern "C" int wisv_profile_enable(wisv_ctx *ctx, int32_t on) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->profiling = on != 0;
+    c->ev_used = 0;
+    memset(c->prof_ms, 0, sizeof c->prof_ms);
+    memset(c->prof_n, 0, sizeof c->prof_n);
+    return WISV_OK;
+}
+
+extern "C" int wisv_profile_collect(wisv_ctx *ctx) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_pool[i], c->ev_pool[i + 1]));
+        c->prof_ms[c->ev_class[i / 2]] += ms;
+        c->prof_n[c->ev_class[i / 2]] += 1;
+    }
+    c->ev_used = 0;
+    return WISV_OK;
+}
+
+extern "C" int wisv_profile_read(wisv_ctx *ctx, int32_t kclass, const char **name, double *total_ms, int64_t *launches) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (kclass < 0 || kclass >= KC_COUNT) return fail(c, WISV_EINVAL, "kernel class %d outside [0, %d)", kclass, (int)KC_COUNT);
+    if (name) *name = kClassNames[kclass];
+    if (total_ms) *total_ms = c->prof_ms[kclass];
+    if (launches) *launches = c->prof_n[kclass];
+    return WISV_OK;
+}

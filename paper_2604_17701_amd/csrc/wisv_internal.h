@@ -1,0 +1,141 @@
+// Internal declarations of the WISV verify-round library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "wisv.h"
+
+namespace wisv {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+// ---------------------------------------------------------------- device-side scalar helpers
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round-to-nearest-even; NaN is kept a NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    __device__ static __forceinline__ float load(const float *p) { return *p; }
+    __device__ static __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    __device__ static __forceinline__ float load(const bf16_t *p) { return bf16_to_f32(*p); }
+    __device__ static __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---------------------------------------------------------------- kernel classes (for per-kernel timing)
+enum KernelClass {
+    KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_ROPE, KC_ATTN, KC_SWIGLU, KC_LMHEAD, KC_ARGMAX,
+    KC_HEAD, KC_DECIDE, KC_COUNT
+};
+
+// ---------------------------------------------------------------- the context
+struct LayerW {
+    void *attn_norm, *wqkv, *wo, *ffn_norm, *wgu, *wdown;
+};
+
+struct Ctx {
+    wisv_config cfg;
+    hipStream_t stream;
+    bool bf16;
+    size_t esz;          // bytes per weight / cache element
+    int d_q, d_kv, d_qkv, rows_max;
+
+    // parameters (private copies)
+    void *embed, *lm_head, *final_norm;
+    std::vector<LayerW> layers;
+    void *head_w1, *head_b1, *head_w2, *head_b2;
+    float *rope_cos, *rope_sin;   // [max_ctx][head_dim/2]
+
+    // KV cache [n_layers][max_batch][2][n_kv_heads][max_ctx][head_dim]
+    void *kv;
+    bool kv_owned;
+
+    // per-slot state (device) and a host mirror holding an upper bound of kv_len
+    int32_t *d_kv_len, *d_pred_next;
+    std::vector<int32_t> h_len_ub;
+
+    // round inputs staged on the device (host-pointer mode)
+    int32_t *d_stream_ids, *d_tokens, *d_proto, *d_hd_row;
+    void *d_hd;
+    float *d_csi, *d_tau;
+    // round outputs staged on the device
+    int32_t *d_alen, *d_ytok, *d_targ;
+    float *d_pacc;
+    uint32_t *d_mask, *d_status;
+
+    // scratch
+    int32_t *row_slot, *row_pos, *amax, *scored;
+    float *x, *y, *qkv, *gu, *h_t, *logits;
+    void *a, *q, *o, *h;          // activation operands (float or bf16)
+    size_t logits_rows;
+
+    // timing
+    hipEvent_t ev_round[2];
+    bool profiling;
+    std::vector<hipEvent_t> ev_pool;
+    std::vector<int> ev_class;
+    size_t ev_used;
+    double prof_ms[KC_COUNT];
+    long prof_n[KC_COUNT];
+    int last_rows;
+
+    std::string err;
+    std::vector<void *> owned;    // device allocations to free
+};
+
+// what one forward needs to know (rows = batch*k; rows of a stream are consecutive)
+struct Fwd {
+    int rows, batch, k;
+    const int32_t *stream_ids;   // device [batch]
+    const int32_t *tokens;       // device [rows]
+    bool keep_logits;
+    int max_len_ub;              // upper bound of kv_len + k over the streams of this forward
+};
+
+// ---------------------------------------------------------------- kernel launchers (kernels_ref.hip)
+void launch_prep_rows(Ctx *c, const Fwd &f);
+void launch_embed(Ctx *c, const Fwd &f);
+// x += sum of n_partial slices of y (if n_partial > 0); out = RMSNorm(x) * g; optional float copy
+void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, void *out, float *out_f32);
+// Y[rows, n] = A[rows, kd] * W[n, kd]^T (float accumulate, float out)
+void launch_gemm_ref(Ctx *c, const void *A, const void *W, float *Y, int rows, int n, int kd, int kclass);
+void launch_rope_append(Ctx *c, const Fwd &f, int layer);
+void launch_attn_ref(Ctx *c, const Fwd &f, int layer);
+void launch_swiglu(Ctx *c, int rows);
+void launch_argmax(Ctx *c, int rows);
+void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in_dev, const wisv_round_out &out_dev);
+void launch_set_pred_next(Ctx *c, int slot, int row, int new_len);
+
+// records the event pair of one launch when profiling is on
+struct ProfScope {
+    Ctx *c;
+    int idx;
+    ProfScope(Ctx *c, int kclass);
+    ~ProfScope();
+};
+
+void *kv_ptr(const Ctx *c, int layer, int slot, int which);   // which: 0 = K, 1 = V
+
+}  // namespace wisv

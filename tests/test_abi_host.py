@@ -1,0 +1,78 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad configurations before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_17701_amd import binding
+from wisv_inputs import configs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    with open(os.path.join(ROOT, "include", "wisv.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wisv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = binding.load_library()
+    names = _declared_symbols()
+    assert {"wisv_ctx_create", "wisv_verify_round", "wisv_destroy"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_struct_sizes_match_the_header_layout():
+    # 7 ints, 2 floats, 9 ints, then three pointer-sized members (8-byte aligned)
+    assert C.sizeof(binding.wisv_config) == 18 * 4 + 3 * 8
+    assert C.sizeof(binding.wisv_round_in) == 8 + 5 * 8 + 8 + 2 * 8 + 8
+    assert C.sizeof(binding.wisv_round_out) == 6 * 8
+    assert C.sizeof(binding.wisv_weights) == 16 * 8
+
+
+def _create(cfg, weights=None):
+    lib = binding.load_library()
+    h = C.c_void_p()
+    err = C.create_string_buffer(256)
+    rc = lib.wisv_ctx_create(C.byref(cfg) if cfg is not None else None, weights, C.byref(h), err, 256)
+    return rc, h, err.value.decode()
+
+
+@pytest.mark.parametrize("field,value,needle", [
+    ("n_layers", 0, "n_layers"), ("d_model", 100, "d_model"), ("n_kv_heads", 3, "n_heads"),
+    ("head_dim", 48, "head_dim"), ("dtype", 7, "dtype"), ("max_k", 17, "max_k"), ("max_ctx", 4, "max_ctx"),
+    ("d_csi", 0, "decision-head"), ("head_act", 5, "head_act"), ("vocab", 1, "vocab"), ("max_batch", 0, "max_batch"),
+])
+def test_create_rejects_bad_config_before_any_gpu_work(field, value, needle):
+    cfg = binding.make_config(configs.TINY, max_batch=1, max_ctx=64, max_k=4)
+    setattr(cfg, field, value)
+    rc, h, msg = _create(cfg)
+    assert rc == binding.WISV_EINVAL and not h.value and needle in msg
+
+
+def test_create_rejects_null_arguments():
+    cfg = binding.make_config(configs.TINY, max_batch=1, max_ctx=64, max_k=4)
+    rc, h, msg = _create(cfg, None)
+    assert rc == binding.WISV_EINVAL and "weights" in msg
+    rc, h, msg = _create(None, None)
+    assert rc == binding.WISV_EINVAL and "config" in msg
+    lib = binding.load_library()
+    assert lib.wisv_ctx_create(C.byref(cfg), None, None, None, 0) == binding.WISV_EINVAL
+    # a borrowed cache that is too small
+    cfg.kv_cache, cfg.kv_bytes = 4096, 16
+    rc, _, msg = _create(cfg, C.pointer(binding.wisv_weights()))
+    assert rc == binding.WISV_EINVAL and "kv_cache" in msg
+
+
+def test_null_context_is_handled():
+    lib = binding.load_library()
+    assert lib.wisv_destroy(None) == binding.WISV_OK
+    assert lib.wisv_verify_round(None, None, None) == binding.WISV_EINVAL
+    assert lib.wisv_last_error(None) == b""
+    assert lib.wisv_set_state(None, 0, 0, 0) == binding.WISV_EINVAL

@@ -1,0 +1,203 @@
+"""GPU parity on the sizes the oracle finishes in seconds: config 0 (tiny fp32, real prefill on both
+sides) and small bf16 decoders spanning several tiles and ragged tails.  Everything goes through the
+C ABI (paper_2604_17701_amd.binding)."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from conftest import have_gpu
+from parity import (OracleSide, TOL_BF16, TOL_F32, check_invariants, compare_stream, row_rel_err, to_host_weights)
+from paper_2604_17701_amd import binding
+from wisv_inputs import configs, gen
+from wisv_inputs.configs import PROTO_FH, PROTO_SH
+
+pytestmark = pytest.mark.gpu
+
+W0 = configs.get(0)
+
+
+def _ctx(w, weights_dev, max_batch=None, extra_ctx=0):
+    return binding.Context(w.model, weights_dev, max_batch or w.batch, w.ctx + w.k + extra_ctx, w.k)
+
+
+def _run_workload(w, tol, kv="prefill", taus=None, keep_logits=True, sampled=None, print_tag=""):
+    """Builds workload w on both sides, runs one round per tau, compares the sampled streams element by
+    element and checks the value-free invariants on all streams."""
+    dev = torch.device("cuda:0")
+    wd = gen.make_weights(w.model, w.seed, dev)
+    side = OracleSide(w, to_host_weights(wd))
+    ctx = _ctx(w, wd)
+    sampled = list(range(w.batch)) if sampled is None else sampled
+    for b in range(w.batch):
+        if kv == "prefill":
+            ctx.wisv_prefill(b, gen.context_tokens(w, b))
+            if b in sampled:
+                side.prefill(b)
+        else:
+            for l in range(w.model.n_layers):
+                k, v = gen.synthetic_kv(w, b, l, dev)
+                ctx.wisv_kv_import(b, l, k, v)
+            ctx.wisv_set_state(b, w.ctx, gen.synthetic_pred_next(w, b))
+            if b in sampled:
+                side.load_synthetic_kv(b, dev)
+    assert sampled == list(range(w.batch)), "small workloads sample every stream"
+    if kv == "prefill":
+        for b in sampled:
+            assert ctx.wisv_get_state(b) == (w.ctx, side.pred_next[b])
+    ins = [side.stream_inputs(b) for b in range(w.batch)]
+    hd, row_map = gen.pack_hidden(w, [s.hd for s in ins], [s.mismatch for s in ins])
+    drafts = np.concatenate([s.draft for s in ins])
+    csi = gen.csi_features(w)
+    stats = {}
+    for tau in (taus or w.taus):
+        flags = binding.WISV_FLAG_NO_COMMIT | (binding.WISV_FLAG_KEEP_LOGITS if keep_logits else 0)
+        g = ctx.wisv_verify_round(np.arange(w.batch), drafts, w.protos, hd, row_map, csi, np.full(w.batch, tau),
+                                  w.k, flags)
+        check_invariants(g, drafts, w.k)
+        logits = ctx.wisv_debug_copy(binding.WISV_DBG_LOGITS, w.m) if keep_logits else None
+        hidden = ctx.wisv_debug_copy(binding.WISV_DBG_HIDDEN, w.m)
+        for b in sampled:
+            rows = row_map[b * w.k:(b + 1) * w.k]
+            o = side.round(b, ins[b], w.protos[b], hd, rows, csi[b], tau, want_logits=keep_logits)
+            if keep_logits:
+                err = row_rel_err(logits[b * w.k:(b + 1) * w.k], o["logits"])
+                stats["logit_rel"] = max(stats.get("logit_rel", 0.0), err)
+                assert err <= tol.logit_rel, f"logits rel err {err}"
+            herr = row_rel_err(hidden[b * w.k:(b + 1) * w.k], o["h_t"])
+            stats["hidden_rel"] = max(stats.get("hidden_rel", 0.0), herr)
+            assert herr <= tol.hidden_rel, f"h^T rel err {herr}"
+            compare_stream(g, b, o, w.k, tau, tol, stats)
+    print(f"\n[{print_tag or w.name}] {stats}", flush=True)
+    ctx.wisv_destroy()
+    return stats
+
+
+def test_generator_is_bit_identical_on_cpu_and_gpu():
+    a = gen.normal(5, "x", (100003,), 0.02, torch.bfloat16, "cpu")
+    b = gen.normal(5, "x", (100003,), 0.02, torch.bfloat16, "cuda:0").cpu()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    c = gen.normal(5, "y", (4099,), 1.0, torch.float32, "cuda:0", start=77).cpu()
+    assert torch.equal(c, gen.normal(5, "y", (4099,), 1.0, torch.float32, "cpu", start=77))
+
+
+def test_config0_tiny_fp32_full_hidden():
+    stats = _run_workload(W0, TOL_F32)
+    assert stats.get("exact", 0) + stats.get("exempt_tie", 0) + stats.get("exempt_tau", 0) == 1
+
+
+def test_config0_threshold_extremes_and_chain_draft():
+    dev = torch.device("cuda:0")
+    w = W0
+    wd = gen.make_weights(w.model, w.seed, dev)
+    ctx = _ctx(w, wd)
+    ctx.wisv_prefill(0, gen.context_tokens(w, 0))
+    _, pn = ctx.wisv_get_state(0)
+    hd, csi = gen.draft_hidden(w, 0), gen.csi_features(w)
+    nc = binding.WISV_FLAG_NO_COMMIT
+
+    def rnd(draft, tau, proto=PROTO_FH, rows=None, flags=nc, hidden=hd):
+        return ctx.wisv_verify_round([0], draft, [proto], hidden, rows, csi, [tau], w.k, flags)
+
+    # a drafter that follows the target's greedy chain is accepted in full at any threshold
+    chain = []
+    for j in range(w.k):
+        probe = chain + [0] * (w.k - j)
+        chain.append(int(rnd(probe, 0.0)["target_argmax"][0, j]))
+    for tau in (0.0, 0.5, 1.5):
+        r = rnd(chain, tau)
+        assert r["accepted_len"][0] == w.k and r["mismatch_mask"][0] == 0
+        assert r["correction_token"][0] == r["target_argmax"][0, w.k]
+    r = rnd(chain, 0.5, proto=PROTO_SH, rows=np.full(w.k, -1), hidden=None)
+    assert r["accepted_len"][0] == w.k and r["status"][0] == 0
+    # every position off the chain: tau = 0 accepts all, tau > 1 leaves only the correction token
+    off = []
+    for j in range(w.k):
+        t = int(rnd(off + [0] * (w.k - j), 0.0)["target_argmax"][0, j])
+        off.append((t + 1 + j) % w.model.vocab)
+    r0, r1 = rnd(off, 0.0), rnd(off, 1.5)
+    assert r0["accepted_len"][0] == w.k and r0["mismatch_mask"][0] == (1 << w.k) - 1
+    assert r1["accepted_len"][0] == 0 and r1["correction_token"][0] == pn
+    assert rnd(chain, 1.5, flags=nc | binding.WISV_FLAG_GATE_ALL)["accepted_len"][0] == 0
+    # selective upload with exactly the mismatch rows reproduces the full upload
+    mixed = [chain[0], off[1] if off[1] != chain[1] else (off[1] + 1) % w.model.vocab] + chain[2:]
+    full = rnd(mixed, 0.45)
+    s = [j for j in range(w.k) if (int(full["mismatch_mask"][0]) >> j) & 1]
+    rows = np.full(w.k, -1, np.int32)
+    rows[s] = np.arange(len(s))
+    sel = rnd(mixed, 0.45, proto=PROTO_SH, rows=rows, hidden=hd[s])
+    assert (sel["accepted_len"][0], sel["correction_token"][0]) == (full["accepted_len"][0], full["correction_token"][0])
+    np.testing.assert_array_equal(sel["p_accept"][0, s], full["p_accept"][0, s])
+    rows[s[0]] = -1
+    miss = rnd(mixed, 0.0, proto=PROTO_SH, rows=rows, hidden=hd[s])
+    assert miss["accepted_len"][0] == s[0] and miss["status"][0] == binding.WISV_STATUS_MISSING_HIDDEN
+    # same inputs, same bits
+    again = rnd(mixed, 0.45)
+    for key in full:
+        assert np.array_equal(full[key], again[key])
+    ctx.wisv_destroy()
+
+
+def test_commit_advances_the_stream_state():
+    dev = torch.device("cuda:0")
+    w = W0
+    wd = gen.make_weights(w.model, w.seed, dev)
+    side = OracleSide(w, to_host_weights(wd))
+    ctx = _ctx(w, wd, extra_ctx=8)
+    ctx.wisv_prefill(0, gen.context_tokens(w, 0))
+    side.prefill(0)
+    si = side.stream_inputs(0)
+    csi = gen.csi_features(w)
+    r = ctx.wisv_verify_round([0], si.draft, [PROTO_FH], si.hd, None, csi, [0.45], w.k, 0)
+    a = int(r["accepted_len"][0])
+    assert ctx.wisv_get_state(0) == (w.ctx + a, int(r["correction_token"][0]))   # L' = L + A; the correction token
+    # the K/V rows the round appended equal the oracle's
+    side.orc.forward_block(side.cache[0], w.ctx, si.draft)
+    for l in range(w.model.n_layers):
+        k, v = ctx.wisv_kv_export(0, l, w.ctx + w.k)
+        np.testing.assert_allclose(k.numpy(), side.cache[0][l, 0], atol=2e-5)
+        np.testing.assert_allclose(v.numpy(), side.cache[0][l, 1], atol=2e-5)
+    ctx.wisv_destroy()
+
+
+def test_round_argument_errors_leave_outputs_untouched():
+    dev = torch.device("cuda:0")
+    w = W0
+    ctx = _ctx(w, gen.make_weights(w.model, w.seed, dev))
+    ctx.wisv_set_state(0, w.ctx, 1)
+    hd, csi = gen.draft_hidden(w, 0), gen.csi_features(w)
+    good = dict(stream_ids=[0], draft_tokens=[1, 2, 3, 4], proto=[0], hd=hd, hd_row=None, csi=csi, tau=[0.5], k=w.k)
+    for change, needle in (({"stream_ids": [3]}, "stream_ids"), ({"draft_tokens": [1, 2, 3, w.model.vocab]}, "vocabulary"),
+                           ({"proto": [2]}, "proto"), ({"hd_row": [0, 1, 2, 9]}, "hd_row"),
+                           ({"hd": hd[:2]}, "identity")):
+        with pytest.raises(binding.WisvError) as e:
+            ctx.wisv_verify_round(**{**good, **change})
+        assert e.value.code == binding.WISV_EINVAL and needle in str(e.value)
+    ctx.wisv_set_state(0, w.ctx + w.k, 1)                       # no room for another block
+    with pytest.raises(binding.WisvError) as e:
+        ctx.wisv_verify_round(**good)
+    assert e.value.code == binding.WISV_ESTATE
+    ctx.wisv_destroy()
+
+
+# ---------------------------------------------------------------- small bf16 decoders (GQA, ragged sizes)
+
+MID = replace(configs.LLAMA8B, n_layers=3, d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, d_ff=1376, vocab=5003,
+              d_draft=192, d_head_hidden=96)
+
+
+@pytest.mark.parametrize("batch,ctx_len,k,protos", [
+    (1, 200, 4, (PROTO_FH,)),
+    (3, 333, 7, (PROTO_FH, PROTO_SH, PROTO_SH)),
+])
+def test_small_bf16_decoder_prefill(batch, ctx_len, k, protos):
+    w = replace(configs.get(1), model=MID, batch=batch, ctx=ctx_len, k=k, protos=protos, kv_source="prefill",
+                name=f"mid_bf16_b{batch}_l{ctx_len}_k{k}", index=7, match_rate=(0.5, 0.5))
+    _run_workload(w, TOL_BF16, kv="prefill")
+
+
+def test_small_bf16_decoder_synthetic_kv():
+    w = replace(configs.get(2), model=replace(MID, head_dim=128, n_heads=4, n_kv_heads=1), batch=2, ctx=1100, k=8,
+                protos=(PROTO_SH, PROTO_FH), name="mid_bf16_synthkv", index=8)
+    _run_workload(w, TOL_BF16, kv="synthetic")
