@@ -22,10 +22,12 @@
  *
  * Arithmetic: activations are float; every dot product, norm and softmax accumulates
  * in double and rounds once.  Weights are float arrays or bf16 bit patterns widened
- * exactly.  With round_bf16 set, the operands a bf16 model hands to its matrix
- * products - normalised activations, rotated q and k, v, attention output, SwiGLU
- * output, LM-head input - are rounded to bf16 (nearest-even) where they are produced;
- * the residual stream, softmax and the decision head stay float.
+ * exactly.  round_bf16 selects what else a bf16 target stores in bf16 (nearest-even):
+ *   bit 0  the KV cache: rotated k and v are rounded when written to the cache;
+ *   bit 1  every operand handed to a matrix product - normalised activations, rotated
+ *          q, k, v, attention output, SwiGLU output, LM-head input - is rounded where
+ *          it is produced (implies bit 0).
+ * The residual stream, softmax and the decision head stay float in every mode.
  *
  * Pinned by tests/test_oracle_*.py: a cache-free fp64 forward composed from PyTorch CPU
  * library routines, closed forms of RMSNorm / RoPE / attention / head, exhaustive
@@ -42,7 +44,7 @@ typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff, vocab;
     float   rms_eps, rope_theta;
     int32_t storage;      /* 0: weights are float; 1: weights are bf16 bit patterns (uint16) */
-    int32_t round_bf16;   /* 1: matrix-product operands rounded to bf16 where produced */
+    int32_t round_bf16;   /* bit 0: KV cache stored in bf16; bit 1: every matrix-product operand rounded */
     int32_t d_draft, d_csi, d_j, head_act;   /* head_act 0: SiLU, 1: ReLU */
 } orc_model;
 
@@ -77,8 +79,11 @@ static inline float wget(const void *w, int storage, size_t i) {
     return storage ? bf16_bits_to_float(((const uint16_t *)w)[i]) : ((const float *)w)[i];
 }
 
-static inline float maybe_round(const orc_model *m, float x) {
-    return m->round_bf16 ? orc_round_bf16(x) : x;
+static inline float maybe_round(const orc_model *m, float x) {      /* matrix-product operands */
+    return (m->round_bf16 & 2) ? orc_round_bf16(x) : x;
+}
+static inline float cache_round(const orc_model *m, float x) {      /* what goes into the KV cache */
+    return (m->round_bf16 & 3) ? orc_round_bf16(x) : x;
 }
 
 /* ------------------------------------------------------------------ building blocks */
@@ -217,8 +222,8 @@ int orc_forward_block(const orc_model *m, const orc_weights *w, float *cache, in
                 float *kh = kk + (size_t)j * dkv + c * hd, *vh = vv + (size_t)j * dkv + c * hd;
                 orc_rope(kh, hd, pos, m->rope_theta);
                 for (int i = 0; i < hd; ++i) {
-                    kc[c * head_stride + (size_t)pos * hd + i] = maybe_round(m, kh[i]);
-                    vc[c * head_stride + (size_t)pos * hd + i] = maybe_round(m, vh[i]);
+                    kc[c * head_stride + (size_t)pos * hd + i] = cache_round(m, kh[i]);
+                    vc[c * head_stride + (size_t)pos * hd + i] = cache_round(m, vh[i]);
                 }
             }
         }

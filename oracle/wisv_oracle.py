@@ -143,19 +143,22 @@ class Oracle:
 
     `weights` maps the canonical names (embed, lm_head, final_norm, attn_norm[l], wq[l], ...,
     head_w1, head_b1, head_w2, head_b2) to CPU torch tensors, float32 or bfloat16, [out, in].
-    round_bf16=True rounds matrix-product operands to bf16 where produced (a bf16 model's
-    data flow); False keeps every activation in float.
+    round_bf16 selects what a bf16 target keeps in bf16 besides its weights:
+      "kv"   the KV cache only (default for bf16 weights): k and v are rounded when cached;
+      "all"  every matrix-product operand is rounded to bf16 where it is produced;
+      "none" nothing (default for float weights).  True / False mean "all" / "none".
     """
 
     def __init__(self, model, weights: Dict[str, object], round_bf16: Optional[bool] = None):
         self.shape = model
         bf16 = model.dtype == "bf16"
         if round_bf16 is None:
-            round_bf16 = bf16
+            round_bf16 = "kv" if bf16 else "none"
+        mode = {"none": 0, False: 0, "kv": 1, "all": 3, True: 3}[round_bf16]
         self._keep = []
         self.m = _Model(model.n_layers, model.d_model, model.n_heads, model.n_kv_heads, model.head_dim,
                         model.d_ff, model.vocab, model.rms_eps, model.rope_theta,
-                        1 if bf16 else 0, 1 if round_bf16 else 0,
+                        1 if bf16 else 0, mode,
                         model.d_draft, model.d_csi, model.d_head_hidden, model.head_act)
         self.w = _Weights()
         want = torch.bfloat16 if bf16 else torch.float32

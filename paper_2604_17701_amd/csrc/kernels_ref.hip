@@ -1,5 +1,5 @@
 // Generic kernels of the verify round: one straightforward kernel per step, templated on the
-// storage type (float or bf16) of weights / cache (WT) and of matrix-product operands (AT).
+// storage type (float or bf16) of weights / cache (WT) and of activations (AT; float in both paths).
 // They serve the fp32 configuration and are the fallback wherever no specialised bf16 kernel
 // applies (prefill chunks, unusual shapes).
 #include "wisv_internal.h"
@@ -109,8 +109,8 @@ void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, void *out, f
     const int d = c->cfg.d_model;
     const size_t stride = (size_t)c->rows_max * d;
     if (c->bf16)
-        hipLaunchKernelGGL((k_rmsnorm<bf16_t, bf16_t>), dim3(rows), dim3(256), 0, c->stream, c->x, c->y, n_partial,
-                           stride, (const bf16_t *)g, d, c->cfg.rms_eps, (bf16_t *)out, out_f32);
+        hipLaunchKernelGGL((k_rmsnorm<bf16_t, float>), dim3(rows), dim3(256), 0, c->stream, c->x, c->y, n_partial,
+                           stride, (const bf16_t *)g, d, c->cfg.rms_eps, (float *)out, out_f32);
     else
         hipLaunchKernelGGL((k_rmsnorm<float, float>), dim3(rows), dim3(256), 0, c->stream, c->x, c->y, n_partial,
                            stride, (const float *)g, d, c->cfg.rms_eps, (float *)out, out_f32);
@@ -151,7 +151,7 @@ void launch_gemm_ref(Ctx *c, const void *A, const void *W, float *Y, int rows, i
     constexpr int MT = 8;
     dim3 grid((n + 3) / 4, (rows + MT - 1) / MT);
     if (c->bf16)
-        hipLaunchKernelGGL((k_gemm_ref<bf16_t, bf16_t, MT>), grid, dim3(256), 0, c->stream, (const bf16_t *)A,
+        hipLaunchKernelGGL((k_gemm_ref<bf16_t, float, MT>), grid, dim3(256), 0, c->stream, (const float *)A,
                            (const bf16_t *)W, Y, rows, n, kd);
     else
         hipLaunchKernelGGL((k_gemm_ref<float, float, MT>), grid, dim3(256), 0, c->stream, (const float *)A,
@@ -161,13 +161,17 @@ void launch_gemm_ref(Ctx *c, const void *A, const void *W, float *Y, int rows, i
 // ------------------------------------------------------------------------------------------ RoPE + KV append
 // grid (rows, H + 2G), block hd/2.  q heads: rotate -> q operand; k heads: rotate -> cache; v heads: copy -> cache
 template <typename WT, typename AT>
-__global__ void k_rope_append(const float *__restrict__ qkv, int H, int G, int hd, const int32_t *__restrict__ row_slot,
+__global__ void k_rope_append(const float *__restrict__ qkv, int n_partial, size_t partial_stride, int H, int G, int hd, const int32_t *__restrict__ row_slot,
                               const int32_t *__restrict__ row_pos, const float *__restrict__ cs,
                               const float *__restrict__ sn, AT *q_out, WT *kv_layer, size_t slot_stride, int max_ctx) {
     const int m = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     const int d_q = H * hd, d_kv = G * hd, pos = row_pos[m];
     const float *src = qkv + (size_t)m * (d_q + 2 * d_kv) + (size_t)hh * hd;
-    const float a = src[i], b = src[i + half];
+    float a = src[i], b = src[i + half];
+    for (int p = 1; p < n_partial; ++p) {   // fixed order: slice 0 + slice 1 + ...
+        a += src[p * partial_stride + i];
+        b += src[p * partial_stride + i + half];
+    }
     const float co = cs[(size_t)pos * half + i], si = sn[(size_t)pos * half + i];
     if (hh < H) {
         AT *dst = q_out + (size_t)m * d_q + (size_t)hh * hd;
@@ -185,19 +189,20 @@ __global__ void k_rope_append(const float *__restrict__ qkv, int H, int G, int h
     }
 }
 
-void launch_rope_append(Ctx *c, const Fwd &f, int layer) {
+void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial) {
+    const size_t pstride = (size_t)c->rows_max * c->d_qkv;
     ProfScope ps(c, KC_ROPE);
     const wisv_config &g = c->cfg;
     const size_t slot_stride = (size_t)2 * g.n_kv_heads * g.max_ctx * g.head_dim;
     dim3 grid(f.rows, g.n_heads + 2 * g.n_kv_heads), block(g.head_dim / 2);
     void *kvl = kv_ptr(c, layer, 0, 0);
     if (c->bf16)
-        hipLaunchKernelGGL((k_rope_append<bf16_t, bf16_t>), grid, block, 0, c->stream, c->qkv, g.n_heads, g.n_kv_heads,
-                           g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, (bf16_t *)c->q, (bf16_t *)kvl,
+        hipLaunchKernelGGL((k_rope_append<bf16_t, float>), grid, block, 0, c->stream, c->qkv, n_partial, pstride, g.n_heads, g.n_kv_heads,
+                           g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, c->q, (bf16_t *)kvl,
                            slot_stride, g.max_ctx);
     else
-        hipLaunchKernelGGL((k_rope_append<float, float>), grid, block, 0, c->stream, c->qkv, g.n_heads, g.n_kv_heads,
-                           g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, (float *)c->q, (float *)kvl,
+        hipLaunchKernelGGL((k_rope_append<float, float>), grid, block, 0, c->stream, c->qkv, n_partial, pstride, g.n_heads, g.n_kv_heads,
+                           g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, c->q, (float *)kvl,
                            slot_stride, g.max_ctx);
 }
 
@@ -257,13 +262,13 @@ void launch_attn_ref(Ctx *c, const Fwd &f, int layer) {
     dim3 grid(f.rows, g.n_heads);
     void *kvl = kv_ptr(c, layer, 0, 0);
     if (c->bf16)
-        hipLaunchKernelGGL((k_attn_ref<bf16_t, bf16_t>), grid, dim3(256), lds, c->stream, (const bf16_t *)c->q,
+        hipLaunchKernelGGL((k_attn_ref<bf16_t, float>), grid, dim3(256), lds, c->stream, (const float *)c->q,
                            (const bf16_t *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, g.max_ctx,
-                           c->row_slot, c->row_pos, (bf16_t *)c->o);
+                           c->row_slot, c->row_pos, c->o);
     else
         hipLaunchKernelGGL((k_attn_ref<float, float>), grid, dim3(256), lds, c->stream, (const float *)c->q,
                            (const float *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, g.max_ctx, c->row_slot,
-                           c->row_pos, (float *)c->o);
+                           c->row_pos, c->o);
 }
 
 // ------------------------------------------------------------------------------------------ SwiGLU
@@ -279,10 +284,7 @@ void launch_swiglu(Ctx *c, int rows) {
     ProfScope ps(c, KC_SWIGLU);
     const int F = c->cfg.d_ff;
     dim3 grid((F + 255) / 256, rows);
-    if (c->bf16)
-        hipLaunchKernelGGL(k_swiglu<bf16_t>, grid, dim3(256), 0, c->stream, c->gu, F, (bf16_t *)c->h);
-    else
-        hipLaunchKernelGGL(k_swiglu<float>, grid, dim3(256), 0, c->stream, c->gu, F, (float *)c->h);
+    hipLaunchKernelGGL(k_swiglu<float>, grid, dim3(256), 0, c->stream, c->gu, F, c->h);
 }
 
 // ------------------------------------------------------------------------------------------ argmax over logits rows

@@ -212,6 +212,29 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
                                   hipMemcpyDeviceToDevice, c->stream));
     }
 
+    // ---- re-tiled copies for the weight-streaming MFMA GEMM (bf16, every reduction length a multiple of 32)
+    c->ws_ok = c->bf16 && d % 32 == 0 && c->d_q % 32 == 0 && F % 32 == 0;
+    c->lm_head_t = nullptr;
+    if (c->ws_ok) {
+        auto retile = [&](void **dst, const void *src, int n_rows, int kd, int pair_rows) -> hipError_t {
+            const int nrb = pair_rows > 0 ? 2 * ws_padded_row_blocks(pair_rows) : ws_padded_row_blocks(n_rows);
+            char *p;
+            hipError_t e = dalloc(c, &p, (size_t)nrb * 16 * kd * 2);
+            if (e != hipSuccess) return e;
+            *dst = p;
+            launch_retile(c, src, n_rows, kd, pair_rows, p, nrb);
+            return hipGetLastError();
+        };
+        CREATE_TRY(retile(&c->lm_head_t, c->lm_head, V, d, 0));
+        for (int l = 0; l < g.n_layers; ++l) {
+            LayerW &L = c->layers[l];
+            CREATE_TRY(retile(&L.wqkv_t, L.wqkv, c->d_qkv, d, 0));
+            CREATE_TRY(retile(&L.wo_t, L.wo, d, c->d_q, 0));
+            CREATE_TRY(retile(&L.wgu_t, L.wgu, 2 * F, d, F));
+            CREATE_TRY(retile(&L.wdown_t, L.wdown, d, F, 0));
+        }
+    }
+
     // ---- rotary tables, computed in double: angle(pos, i) = pos * theta^(-2i/hd)
     {
         const int half = g.head_dim / 2;
@@ -269,21 +292,19 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     CREATE_TRY(dalloc(c, &c->amax, R));
     CREATE_TRY(dalloc(c, &c->scored, R));
     CREATE_TRY(dalloc(c, &c->x, (size_t)R * d));
-    CREATE_TRY(dalloc(c, &c->y, (size_t)R * d));
-    CREATE_TRY(dalloc(c, &c->qkv, (size_t)R * c->d_qkv));
+    CREATE_TRY(dalloc(c, &c->y, (size_t)MAX_SPLITS * R * d));
+    CREATE_TRY(dalloc(c, &c->qkv, (size_t)MAX_SPLITS * R * c->d_qkv));
+    {
+        const size_t n_cand = ws_padded_row_blocks(V);
+        CREATE_TRY(dalloc(c, &c->cand_val, (size_t)R * n_cand));
+        CREATE_TRY(dalloc(c, &c->cand_idx, (size_t)R * n_cand));
+    }
     CREATE_TRY(dalloc(c, &c->gu, (size_t)R * 2 * F));
     CREATE_TRY(dalloc(c, &c->h_t, (size_t)R * d));
-    {
-        char *p;
-        CREATE_TRY(dalloc(c, &p, (size_t)R * d * esz));
-        c->a = p;
-        CREATE_TRY(dalloc(c, &p, (size_t)R * c->d_q * esz));
-        c->q = p;
-        CREATE_TRY(dalloc(c, &p, (size_t)R * c->d_q * esz));
-        c->o = p;
-        CREATE_TRY(dalloc(c, &p, (size_t)R * F * esz));
-        c->h = p;
-    }
+    CREATE_TRY(dalloc(c, &c->a, (size_t)R * d));
+    CREATE_TRY(dalloc(c, &c->q, (size_t)R * c->d_q));
+    CREATE_TRY(dalloc(c, &c->o, (size_t)R * c->d_q));
+    CREATE_TRY(dalloc(c, &c->h, (size_t)R * F));
     CREATE_TRY(dalloc(c, &c->logits, (size_t)R * V));
     c->logits_rows = R;
     CREATE_TRY(hipStreamSynchronize(c->stream));
@@ -309,11 +330,47 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
     const int d = g.d_model, F = g.d_ff;
     launch_prep_rows(c, f);
     launch_embed(c, f);
+    if (c->ws_ok && f.rows <= 96) {
+        // bf16 weight-streaming path: every product leaves k-split partial slices that the next
+        // kernel sums in a fixed order; gate/up and the LM head fuse SwiGLU / argmax instead
+        const size_t ys = (size_t)c->rows_max * d, qs = (size_t)c->rows_max * c->d_qkv;
+        // a product whose shape the streaming kernel cannot serve falls back to the generic kernel (one slice)
+        auto product = [&](const void *wt, const void *w, const float *X, float *Yp, size_t stride, int n, int kd) {
+            int ns = launch_gemm_ws_partial(c, wt, X, Yp, stride, MAX_SPLITS, f.rows, n, kd, KC_GEMM);
+            if (!ns) {
+                launch_gemm_ref(c, X, w, Yp, f.rows, n, kd, KC_GEMM);
+                ns = 1;
+            }
+            return ns;
+        };
+        int ny = 0;
+        for (int l = 0; l < g.n_layers; ++l) {
+            const LayerW &L = c->layers[l];
+            launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
+            const int nq = product(L.wqkv_t, L.wqkv, c->a, c->qkv, qs, c->d_qkv, d);
+            launch_rope_append(c, f, l, nq);
+            launch_attn_ref(c, f, l);
+            ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
+            launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
+            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, 2 * F, d, KC_GEMM)) {
+                launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM);
+                launch_swiglu(c, f.rows);
+            }
+            ny = product(L.wdown_t, L.wdown, c->h, c->y, ys, d, F);
+        }
+        launch_rmsnorm(c, f.rows, ny, c->final_norm, c->a, c->h_t);
+        if (!launch_gemm_ws_argmax(c, c->lm_head_t, c->a, f.keep_logits ? c->logits : nullptr, f.rows, g.vocab, d,
+                                   KC_LMHEAD)) {
+            launch_gemm_ref(c, c->a, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
+            launch_argmax(c, f.rows);
+        }
+        return;
+    }
     for (int l = 0; l < g.n_layers; ++l) {
         const LayerW &L = c->layers[l];
         launch_rmsnorm(c, f.rows, l == 0 ? 0 : 1, L.attn_norm, c->a, nullptr);     // + previous FFN update
         launch_gemm_ref(c, c->a, L.wqkv, c->qkv, f.rows, c->d_qkv, d, KC_GEMM);
-        launch_rope_append(c, f, l);
+        launch_rope_append(c, f, l, 1);
         launch_attn_ref(c, f, l);
         launch_gemm_ref(c, c->o, L.wo, c->y, f.rows, d, c->d_q, KC_GEMM);
         launch_rmsnorm(c, f.rows, 1, L.ffn_norm, c->a, nullptr);                   // + attention update

@@ -53,6 +53,7 @@ enum KernelClass {
 // ---------------------------------------------------------------- the context
 struct LayerW {
     void *attn_norm, *wqkv, *wo, *ffn_norm, *wgu, *wdown;
+    void *wqkv_t, *wo_t, *wgu_t, *wdown_t;   // re-tiled copies for the weight-streaming GEMM (bf16 only)
 };
 
 struct Ctx {
@@ -63,7 +64,8 @@ struct Ctx {
     int d_q, d_kv, d_qkv, rows_max;
 
     // parameters (private copies)
-    void *embed, *lm_head, *final_norm;
+    void *embed, *lm_head, *final_norm, *lm_head_t;
+    bool ws_ok;          // shapes allow the weight-streaming MFMA GEMM
     std::vector<LayerW> layers;
     void *head_w1, *head_b1, *head_w2, *head_b2;
     float *rope_cos, *rope_sin;   // [max_ctx][head_dim/2]
@@ -87,8 +89,10 @@ struct Ctx {
 
     // scratch
     int32_t *row_slot, *row_pos, *amax, *scored;
-    float *x, *y, *qkv, *gu, *h_t, *logits;
-    void *a, *q, *o, *h;          // activation operands (float or bf16)
+    float *x, *y, *qkv, *gu, *h_t, *logits;   // y and qkv hold up to MAX_SPLITS partial slices
+    float *cand_val;
+    int32_t *cand_idx;
+    float *a, *q, *o, *h;         // activations handed to the matrix products (float in both paths)
     size_t logits_rows;
 
     // timing
@@ -121,12 +125,22 @@ void launch_embed(Ctx *c, const Fwd &f);
 void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, void *out, float *out_f32);
 // Y[rows, n] = A[rows, kd] * W[n, kd]^T (float accumulate, float out)
 void launch_gemm_ref(Ctx *c, const void *A, const void *W, float *Y, int rows, int n, int kd, int kclass);
-void launch_rope_append(Ctx *c, const Fwd &f, int layer);
+void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial);
 void launch_attn_ref(Ctx *c, const Fwd &f, int layer);
 void launch_swiglu(Ctx *c, int rows);
 void launch_argmax(Ctx *c, int rows);
 void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in_dev, const wisv_round_out &out_dev);
 void launch_set_pred_next(Ctx *c, int slot, int row, int new_len);
+
+// ---------------------------------------------------------------- weight-streaming GEMM (kernels_gemm.hip)
+constexpr int MAX_SPLITS = 8;
+bool ws_supported(const Ctx *c, int rows, int kd);
+int ws_padded_row_blocks(int n_rows);
+void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb);
+int launch_gemm_ws_partial(Ctx *c, const void *Wt, const void *X, float *Yp, size_t split_stride, int max_splits,
+                           int rows, int n, int kd, int kclass);
+bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const void *X, void *H, int rows, int two_f, int kd, int kclass);
+bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const void *X, float *logits, int rows, int n, int kd, int kclass);
 
 // records the event pair of one launch when profiling is on
 struct ProfScope {

@@ -26,9 +26,11 @@ class Tolerance:
 
 # fp32 path: only summation order differs between the two sides.
 TOL_F32 = Tolerance(p_abs=1e-5, logit_rel=1e-5, hidden_rel=1e-5, tie_margin_rel=0.0, tie_margin_abs=2e-5, tau_margin=1e-5)
-# bf16 path against the oracle with the same bf16 rounding points: float accumulation order, one-ulp flips
-# of rounded operands and the bf16 probabilities of the attention's P.V product remain.
-TOL_BF16 = Tolerance(p_abs=1e-3, logit_rel=2e-2, hidden_rel=2e-2, tie_margin_rel=2e-2, tie_margin_abs=0.0, tau_margin=1e-3)
+# bf16 path (bf16 weights and KV cache, float activations fed to the matrix cores as two bf16 terms) against
+# the oracle in its matching mode (bf16 weights, KV cache rounded to bf16, float activations).  What remains:
+# float accumulation order, the 2^-17 residue of the two-term split, and rare one-ulp flips of cached k / v.
+# The stated bounds are 2e-2 on logits and 1e-3 on probabilities; the path is held to far tighter ones.
+TOL_BF16 = Tolerance(p_abs=1e-4, logit_rel=1e-3, hidden_rel=1e-3, tie_margin_rel=2e-2, tie_margin_abs=0.0, tau_margin=1e-4)
 
 
 def to_host_weights(weights: Dict[str, object]) -> Dict[str, object]:
@@ -51,6 +53,7 @@ class OracleSide:
         self.orc = wo.Oracle(w.model, host_weights, round_bf16)
         self.cache: Dict[int, np.ndarray] = {}
         self.pred_next: Dict[int, int] = {}
+        self._memo: Dict[int, dict] = {}
 
     def prefill(self, stream: int):
         c = self.orc.new_cache(self.w.ctx + self.w.k)
@@ -67,10 +70,15 @@ class OracleSide:
         self.pred_next[stream] = gen.synthetic_pred_next(self.w, stream)
 
     def next_token_fn(self, stream: int):
+        memo = self._memo.setdefault(stream, {})
+
         def nt(prefix):
             if not prefix:
                 return self.pred_next[stream]
-            return int(self.orc.forward_block(self.cache[stream], self.w.ctx, prefix)["argmax"][-1])
+            key = tuple(int(t) for t in prefix)
+            if key not in memo:
+                memo[key] = int(self.orc.forward_block(self.cache[stream], self.w.ctx, list(key))["argmax"][-1])
+            return memo[key]
         return nt
 
     def stream_inputs(self, stream: int) -> StreamInputs:
@@ -92,12 +100,15 @@ def row_rel_err(a: np.ndarray, ref: np.ndarray) -> float:
 
 
 def compare_stream(gpu: Dict[str, np.ndarray], b: int, orc: Dict[str, object], k: int, tau: float, tol: Tolerance,
-                   stats: Dict[str, int]):
+                   stats: Dict[str, int], gpu_logits: Optional[np.ndarray] = None):
     """Compares stream b of a GPU round with the oracle's round of that stream.
 
     Integers must match exactly.  The only licence: a position where the oracle's own top-1 lead is within
     the tie margin, or whose oracle accept probability is within tau_margin of tau, may decide either way;
     what depends on such a position (the rest of the stream's round) is then counted as exempt, not compared.
+    The tie margin is the stated ceiling (tie_margin_rel * |top1|, or tie_margin_abs); when the GPU's logits
+    of the stream's rows are given it is tightened to twice the largest logit deviation seen in that row,
+    which is what a change of argmax needs.
     """
     t_g, t_o = gpu["target_argmax"][b], orc["t"]
     assert t_g[0] == t_o[0], "pred_next differs"
@@ -105,9 +116,12 @@ def compare_stream(gpu: Dict[str, np.ndarray], b: int, orc: Dict[str, object], k
     for j in range(k):                                         # t[j+1] comes from logits row j
         if t_g[j + 1] != t_o[j + 1]:
             lead = float(orc["gap"][j])
-            top1 = abs(float(orc["top1"][j])) if "top1" in orc else 0.0
-            assert lead <= max(tol.tie_margin_abs, tol.tie_margin_rel * top1), \
-                f"stream {b} row {j}: target token {t_g[j + 1]} != {t_o[j + 1]} with oracle lead {lead}"
+            margin = max(tol.tie_margin_abs, tol.tie_margin_rel * abs(float(orc["top1"][j])))
+            if gpu_logits is not None and orc.get("logits") is not None:
+                dev = float(np.max(np.abs(gpu_logits[j].astype(np.float64) - orc["logits"][j])))
+                margin = min(margin, 2.0 * dev)
+            assert lead <= margin, \
+                f"stream {b} row {j}: target token {t_g[j + 1]} != {t_o[j + 1]}, oracle lead {lead} > margin {margin}"
             stats["exempt_tie"] = stats.get("exempt_tie", 0) + 1
             return
     assert int(gpu["mismatch_mask"][b]) == orc["mismatch_mask"]

@@ -13,9 +13,17 @@ def _bf(x, on):
     return x.to(torch.bfloat16).double() if on else x
 
 
+def _modes(round_bf16):
+    """(round every matrix-product operand, round k and v as cached)."""
+    if round_bf16 == "kv":
+        return False, True
+    return bool(round_bf16), bool(round_bf16)
+
+
 def full_forward(weights, shape, tokens, round_bf16=False):
     """tokens: 1-D int tensor of the whole sequence.  Returns (logits [n, V], h_t [n, d]) float64."""
     d64 = lambda t: t.double()
+    round_bf16, round_kv = _modes(round_bf16)
     n = tokens.numel()
     H, G, hd = shape.n_heads, shape.n_kv_heads, shape.head_dim
     half = hd // 2
@@ -23,8 +31,9 @@ def full_forward(weights, shape, tokens, round_bf16=False):
     def norm(x, g):
         return x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + shape.rms_eps) * d64(g)
 
-    pos = torch.arange(n, dtype=torch.float64)
-    inv_freq = shape.rope_theta ** (-torch.arange(0, hd, 2, dtype=torch.float64) / hd)
+    dev = tokens.device
+    pos = torch.arange(n, dtype=torch.float64, device=dev)
+    inv_freq = shape.rope_theta ** (-torch.arange(0, hd, 2, dtype=torch.float64, device=dev) / hd)
     ang = pos[:, None] * inv_freq[None, :]                    # [n, hd/2]
     cos, sin = ang.cos(), ang.sin()
 
@@ -38,7 +47,7 @@ def full_forward(weights, shape, tokens, round_bf16=False):
         q = F.linear(a, d64(weights["wq"][l])).view(n, H, hd).transpose(0, 1)
         k = F.linear(a, d64(weights["wk"][l])).view(n, G, hd).transpose(0, 1)
         v = F.linear(a, d64(weights["wv"][l])).view(n, G, hd).transpose(0, 1)
-        q, k, v = _bf(rope(q), round_bf16), _bf(rope(k), round_bf16), _bf(v, round_bf16)
+        q, k, v = _bf(rope(q), round_bf16), _bf(rope(k), round_kv), _bf(v, round_kv)
         k = k.repeat_interleave(H // G, dim=0)
         v = v.repeat_interleave(H // G, dim=0)
         o = F.scaled_dot_product_attention(q, k, v, is_causal=True)

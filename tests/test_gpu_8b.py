@@ -1,0 +1,125 @@
+"""GPU parity at the full sizes of configs 1-4 (Llama-3-8B-shaped bf16 target), in the launch
+configuration bench.py times.  The KV cache contents and pred_next are seeded synthetic inputs generated
+identically for both sides; the oracle recomputes sampled streams in full (every row, every logit), the
+value-free invariants are checked on all streams."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from parity import OracleSide, TOL_BF16, check_invariants, compare_stream, row_rel_err, to_host_weights
+from paper_2604_17701_amd import binding
+from wisv_inputs import configs, gen
+from wisv_inputs.configs import PROTO_FH, PROTO_SH
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def target8b():
+    t0 = time.time()
+    w1 = configs.get(1)
+    wd = gen.make_weights(w1.model, w1.seed, DEV)      # the same target serves configs 1-4
+    wh = to_host_weights(wd)
+    print(f"\n[8b weights] generated + copied to host in {time.time() - t0:.1f}s", flush=True)
+    return wd, wh
+
+
+def _gpu_chain_drafts(ctx, w, pred_next):
+    """Drafts of every stream built against the HIP path's own greedy chain (input construction for the
+    streams the oracle does not look at): position j needs the target token after drafts 0..j-1."""
+    drafts = np.zeros((w.batch, w.k), np.int32)
+    plans = [gen.draft_plan(w, b) for b in range(w.batch)]
+    csi = gen.csi_features(w)
+    for j in range(w.k):
+        if j == 0:
+            t = np.asarray(pred_next)
+        else:
+            r = ctx.wisv_verify_round(np.arange(w.batch), drafts, w.protos, None, np.full(w.m, -1), csi,
+                                      np.zeros(w.batch), w.k, binding.WISV_FLAG_NO_COMMIT)
+            t = r["target_argmax"][:, j]
+        for b in range(w.batch):
+            keep, alt = plans[b]
+            a = int(alt[j])
+            drafts[b, j] = int(t[b]) if keep[j] else (a if a != int(t[b]) else (a + 1) % w.model.vocab)
+    return drafts
+
+
+def _run(w, target8b, sampled, tol=TOL_BF16):
+    wd, wh = target8b
+    t0 = time.time()
+    m = w.model
+    max_ctx = w.ctx + w.k
+    kv = torch.zeros((m.n_layers, w.batch, 2, m.n_kv_heads, max_ctx, m.head_dim), dtype=torch.bfloat16, device=DEV)
+    ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
+    side = OracleSide(w, wh)
+    pred_next = []
+    for b in range(w.batch):
+        for l in range(m.n_layers):
+            k, v = gen.synthetic_kv(w, b, l, DEV)
+            kv[l, b, 0, :, :w.ctx] = k
+            kv[l, b, 1, :, :w.ctx] = v
+        pn = gen.synthetic_pred_next(w, b)
+        pred_next.append(pn)
+        ctx.wisv_set_state(b, w.ctx, pn)
+    torch.cuda.synchronize()
+    print(f"\n[{w.name}] cache filled at {time.time() - t0:.1f}s", flush=True)
+    for b in sampled:
+        side.load_synthetic_kv(b, DEV)
+    drafts = _gpu_chain_drafts(ctx, w, pred_next) if len(sampled) < w.batch else np.zeros((w.batch, w.k), np.int32)
+    ins = {b: side.stream_inputs(b) for b in sampled}     # the oracle's chain decides the sampled streams
+    for b in sampled:
+        drafts[b] = ins[b].draft
+    print(f"[{w.name}] drafts built at {time.time() - t0:.1f}s", flush=True)
+    hds = [ins[b].hd if b in ins else gen.draft_hidden(w, b) for b in range(w.batch)]
+    # mismatch sets for the SH upload: the oracle's for sampled streams, the HIP path's own for the rest
+    probe = ctx.wisv_verify_round(np.arange(w.batch), drafts, w.protos, None, np.full(w.m, -1), gen.csi_features(w),
+                                  np.zeros(w.batch), w.k, binding.WISV_FLAG_NO_COMMIT)
+    mism = [ins[b].mismatch if b in ins else [j for j in range(w.k) if (int(probe["mismatch_mask"][b]) >> j) & 1]
+            for b in range(w.batch)]
+    hd, row_map = gen.pack_hidden(w, hds, mism)
+    csi = gen.csi_features(w)
+    stats, prev_a = {}, None
+    for tau in w.taus:
+        g = ctx.wisv_verify_round(np.arange(w.batch), drafts.reshape(-1), w.protos, hd, row_map, csi,
+                                  np.full(w.batch, tau), w.k, binding.WISV_FLAG_NO_COMMIT | binding.WISV_FLAG_KEEP_LOGITS)
+        check_invariants(g, drafts, w.k)
+        if prev_a is not None:
+            assert np.all(g["accepted_len"] <= prev_a), "accepted length must not grow with tau"
+        prev_a = g["accepted_len"].copy()
+        logits = ctx.wisv_debug_copy(binding.WISV_DBG_LOGITS, w.m)
+        hidden = ctx.wisv_debug_copy(binding.WISV_DBG_HIDDEN, w.m)
+        for b in sampled:
+            rows = slice(b * w.k, (b + 1) * w.k)
+            o = side.round(b, ins[b], w.protos[b], hd, row_map[rows], csi[b], tau, want_logits=True)
+            err, herr = row_rel_err(logits[rows], o["logits"]), row_rel_err(hidden[rows], o["h_t"])
+            stats["logit_rel"] = max(stats.get("logit_rel", 0.0), err)
+            stats["hidden_rel"] = max(stats.get("hidden_rel", 0.0), herr)
+            assert err <= tol.logit_rel and herr <= tol.hidden_rel, (err, herr)
+            compare_stream(g, b, o, w.k, tau, tol, stats, logits[rows])
+        stats[f"mean_A@{tau}"] = float(np.mean(g["accepted_len"]))
+        print(f"[{w.name}] tau={tau} compared at {time.time() - t0:.1f}s", flush=True)
+    print(f"[{w.name}] {stats}", flush=True)
+    ctx.wisv_destroy()
+    del kv
+    torch.cuda.empty_cache()
+    return stats
+
+
+def test_config1_batch1_ctx512_k4_full_hidden(target8b):
+    _run(configs.get(1), target8b, sampled=[0])
+
+
+def test_config2_batch1_ctx4096_k8_selective_hidden(target8b):
+    _run(configs.get(2), target8b, sampled=[0])
+
+
+def test_config3_batch16_ctx2048_k6_tau_sweep(target8b):
+    _run(configs.get(3), target8b, sampled=[0, 11])
+
+
+def test_config4_batch64_ctx8192_k8_mixed_protocols(target8b):
+    _run(configs.get(4), target8b, sampled=[5, 38])     # one SH (odd) and one FH (even) stream

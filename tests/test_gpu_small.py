@@ -68,7 +68,7 @@ def _run_workload(w, tol, kv="prefill", taus=None, keep_logits=True, sampled=Non
             herr = row_rel_err(hidden[b * w.k:(b + 1) * w.k], o["h_t"])
             stats["hidden_rel"] = max(stats.get("hidden_rel", 0.0), herr)
             assert herr <= tol.hidden_rel, f"h^T rel err {herr}"
-            compare_stream(g, b, o, w.k, tau, tol, stats)
+            compare_stream(g, b, o, w.k, tau, tol, stats, logits[b * w.k:(b + 1) * w.k] if keep_logits else None)
     print(f"\n[{print_tag or w.name}] {stats}", flush=True)
     ctx.wisv_destroy()
     return stats

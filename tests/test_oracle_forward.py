@@ -205,3 +205,29 @@ def test_bf16_rounding_points_against_library_forward():
     orc_r.forward_block(c, 0, toks)
     ct = torch.from_numpy(c)
     assert torch.equal(ct.to(torch.bfloat16).float(), ct)
+
+
+def test_bf16_cache_only_mode_rounds_exactly_the_cached_k_and_v():
+    shape = _bf16_shape()
+    wb = gen.make_weights(shape, 33)
+    toks = gen.randint(33, "t", (12,), shape.vocab).to(torch.int32)
+    orc_kv = wo.Oracle(shape, wb)                       # default for bf16 weights: "kv"
+    orc_n = wo.Oracle(shape, wb, round_bf16="none")
+    ck, cn = orc_kv.new_cache(12), orc_n.new_cache(12)
+    # one token: nothing cached is read back yet, so the logits agree and the cache is the rounded float cache
+    a = orc_kv.forward_block(ck, 0, toks[:1], want_logits=True)
+    b = orc_n.forward_block(cn, 0, toks[:1], want_logits=True)
+    layer0 = (slice(0, 1), slice(None), slice(None), slice(0, 1))
+    assert np.array_equal(ck[layer0], torch.from_numpy(cn[layer0]).to(torch.bfloat16).float().numpy())
+    assert not np.array_equal(ck[layer0], cn[layer0])
+    # a single position attends only to itself with weight 1: its output is the cached (rounded) v, so the two
+    # modes differ from the first layer on, by about one bf16 rounding of v
+    rel = np.abs(a["logits"] - b["logits"]).max() / np.abs(b["logits"]).max()
+    assert 0 < rel < 3e-2
+    # against the library forward with the same two rounding points
+    ref, _ = full_forward(wb, shape, toks, round_bf16="kv")
+    z = orc_kv.forward_block(orc_kv.new_cache(12), 0, toks, want_logits=True)["logits"]
+    zn = orc_n.forward_block(orc_n.new_cache(12), 0, toks, want_logits=True)["logits"]
+    d_same = np.sqrt(np.mean((z - ref.numpy()) ** 2))
+    d_round = np.sqrt(np.mean((z.astype(np.float64) - zn) ** 2))
+    assert d_round > 0 and d_same < 0.2 * d_round, (d_same, d_round)
