@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the WISV edge-side verification round on one MI355X.
+
+One step = one whole verify round (target forward over the K drafted tokens of every stream against the
+KV cache, decision head, first-reject scan) on synthetic inputs already resident in HBM.
+Prints ONE JSON line: verified draft tokens/s and ms per round, the roofline of the dominant kernel
+(HIP-event durations measured here), and the CPU oracle timed on the host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def build_round(ctx, w, binding, gen, np, torch):
+    """Synthetic cache contents, drafts (built against the path's own greedy chain at the workload's match
+    rate), drafter hidden states and CSI for workload w; returns a DeviceRound ready to be re-enqueued."""
+    dev = "cuda:0"
+    pred_next = []
+    for b in range(w.batch):
+        for l in range(w.model.n_layers):
+            k, v = gen.synthetic_kv(w, b, l, dev)
+            ctx._kv[l, b, 0, :, :w.ctx] = k
+            ctx._kv[l, b, 1, :, :w.ctx] = v
+        pn = gen.synthetic_pred_next(w, b)
+        pred_next.append(pn)
+        ctx.wisv_set_state(b, w.ctx, pn)
+    csi = gen.csi_features(w)
+    sid = np.arange(w.batch)
+    drafts = np.zeros((w.batch, w.k), np.int32)
+    plans = [gen.draft_plan(w, b) for b in range(w.batch)]
+    nc = binding.WISV_FLAG_NO_COMMIT
+    for j in range(w.k):
+        if j == 0:
+            t = np.asarray(pred_next)
+        else:
+            r = ctx.wisv_verify_round(sid, drafts, w.protos, None, np.full(w.m, -1), csi, np.zeros(w.batch), w.k, nc)
+            t = r["target_argmax"][:, j]
+        for b in range(w.batch):
+            keep, alt = plans[b]
+            a = int(alt[j])
+            drafts[b, j] = int(t[b]) if (keep[j] and not w.uniform_drafts) else \
+                (a if a != int(t[b]) else (a + 1) % w.model.vocab)
+    probe = ctx.wisv_verify_round(sid, drafts, w.protos, None, np.full(w.m, -1), csi, np.zeros(w.batch), w.k, nc)
+    mism = [[j for j in range(w.k) if (int(probe["mismatch_mask"][b]) >> j) & 1] for b in range(w.batch)]
+    hd, row_map = gen.pack_hidden(w, [gen.draft_hidden(w, b) for b in range(w.batch)], mism)
+    tau = np.full(w.batch, w.taus[len(w.taus) // 2], np.float32)
+    rnd = ctx.device_round(sid, drafts, w.protos, hd if hd.shape[0] else None, row_map, csi, tau, w.k, nc)
+    return rnd, dict(drafts=drafts, hd=hd, row_map=row_map, csi=csi, tau=tau, pred_next=pred_next)
+
+
+def cpu_baseline(w, weights_dev, inputs, gen, np, torch, budget_s=20.0):
+    """The oracle, as it stands, on the host cores: whole rounds of stream 0 of the same workload."""
+    from oracle import wisv_oracle as wo
+    wh = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in weights_dev.items()}
+    orc = wo.Oracle(w.model, wh)
+    cache = orc.new_cache(w.ctx + w.k)
+    for l in range(w.model.n_layers):
+        k, v = gen.synthetic_kv(w, 0, l, "cuda:0")
+        cache[l, 0, :, :w.ctx] = k.float().cpu().numpy()
+        cache[l, 1, :, :w.ctx] = v.float().cpu().numpy()
+    rows = inputs["row_map"][:w.k]
+    args = (cache, w.ctx, inputs["pred_next"][0], inputs["drafts"][0], w.protos[0], inputs["hd"], rows,
+            inputs["csi"][0], float(inputs["tau"][0]))
+    orc.verify_round(*args)                                    # warm-up
+    times = []
+    t_start = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_start < budget_s and len(times) < 20):
+        t0 = time.perf_counter()
+        orc.verify_round(*args)
+        times.append(time.perf_counter() - t0)
+    med = sorted(times)[len(times) // 2]
+    return {"value": w.k / med, "unit": "verified draft tokens/s", "cores": wo.num_threads(), "kind": "oracle",
+            "sample": f"{len(times)} whole rounds of one stream (K={w.k}, context {w.ctx}) of this workload, "
+                      f"median {med * 1e3:.1f} ms per round; one stream of {w.batch}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default: the headline one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: the verify round runs on ONE GPU (streams are independent; nothing is sharded): "
+                 "run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2604_17701_amd import binding
+    from wisv_inputs import configs, gen
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU: the verify round has no CPU implementation")
+    w = configs.get(a.config)
+    dev = "cuda:0"
+    t0 = time.time()
+    wd = gen.make_weights(w.model, w.seed if a.config == 0 else configs.get(1).seed, dev)
+    m = w.model
+    max_ctx = w.ctx + w.k
+    kv = torch.zeros((m.n_layers, w.batch, 2, m.n_kv_heads, max_ctx, m.head_dim), dtype=gen.torch_dtype(m), device=dev)
+    ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
+    rnd, inputs = build_round(ctx, w, binding, gen, np, torch)
+    log(f"{w.name}: inputs resident after {time.time() - t0:.1f}s")
+
+    # ---- the timed region: exactly `steps` rounds between two synchronisations
+    for _ in range(a.warmup):
+        rnd.run()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(a.steps):
+        rnd.run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms = elapsed / a.steps * 1e3
+    res = rnd.results()
+    verified = w.batch * w.k / (ms * 1e-3)
+
+    # ---- per-kernel durations: the same rounds again with a HIP event pair around every launch
+    ctx.wisv_profile_enable(True)
+    for _ in range(a.steps):
+        rnd.run()
+    ctx.wisv_profile_collect()
+    prof = ctx.wisv_profile_read()
+    ctx.wisv_profile_enable(False)
+    kernels = {n: {"ms_per_round": t / a.steps, "launches_per_round": c // a.steps, "avg_us": 1e3 * t / max(c, 1)}
+               for n, (t, c) in prof.items() if c}
+    # algorithmic bytes each weight-streaming kernel class must read per round
+    esz = 2 if m.dtype == "bf16" else 4
+    d, f, nl = m.d_model, m.d_ff, m.n_layers
+    alg_bytes = {
+        "gemm_gate_up": nl * 2 * f * d * esz,
+        "gemm_qkv_o_down": nl * (d * (m.d_q + 2 * m.d_kv) + m.d_q * d + d * f) * esz,
+        "lm_head": m.vocab * d * esz,
+        "attention": w.batch * w.ctx * m.kv_bytes_per_token(),
+    }
+    dom = max((n for n in alg_bytes if n in kernels), key=lambda n: kernels[n]["ms_per_round"])
+    k = kernels[dom]
+    per_launch = alg_bytes[dom] / k["launches_per_round"]
+    achieved = per_launch / (k["avg_us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "bytes_per_launch": per_launch, "avg_launch_us": k["avg_us"],
+                "timing": f"HIP event pair around every launch on the round's stream, {a.steps} rounds right after the timed ones"}
+    round_alg = w.algorithmic_bytes()
+    out = {
+        "metric": "verified draft tokens/sec + ms per verify round, 8B-shaped target, K=4",
+        "value": verified, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if m.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "context": w.ctx, "k": w.k, "rows": w.m,
+                   "protocols": "FH" if set(w.protos) == {0} else ("SH" if set(w.protos) == {1} else "FH+SH"),
+                   "tau": float(inputs["tau"][0])},
+        "roofline": roofline,
+        "round_hbm": {"algorithmic_bytes": round_alg, "achieved_GBs": round_alg / (ms * 1e-3) / 1e9,
+                      "frac_of_peak": round_alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "accepted_tokens_per_s": float(res["accepted_len"].sum()) / (ms * 1e-3),
+        "committed_tokens_per_s": float((res["accepted_len"] + 1).sum()) / (ms * 1e-3),
+        "mean_accepted_len": float(res["accepted_len"].mean()),
+        "kernels": kernels,
+    }
+    if not a.no_cpu_baseline:
+        t2 = time.time()
+        out["cpu_baseline"] = cpu_baseline(w, wd, inputs, gen, np, torch)
+        log(f"cpu baseline took {time.time() - t2:.1f}s")
+    ctx.wisv_destroy()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -36,6 +36,7 @@
  * 8B-shaped workloads have no printed example in the paper to compare with.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -291,6 +292,17 @@ void orc_head(const orc_model *m, const orc_weights *w, const float *h_d, const 
     *s_out = (float)s;
     *p_rej = (float)(1.0 / (1.0 + exp(-s)));
     *p_acc = (float)(1.0 / (1.0 + exp(s)));
+}
+
+/* number of threads the parallel loops above run on */
+int orc_num_threads(void) {
+    int n = 1;
+#pragma omp parallel
+    {
+#pragma omp single
+        n = omp_get_num_threads();
+    }
+    return n;
 }
 
 /* FLOPs of one head evaluation as the paper counts them: 2 d_in d_J + d_J + 2 d_J + 1 */

@@ -82,6 +82,10 @@ def round_bf16(x: float) -> float:
     return float(lib().orc_round_bf16(C.c_float(x)))
 
 
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
 def head_flops(d_in: int, d_j: int) -> int:
     return int(lib().orc_head_flops(d_in, d_j))
 

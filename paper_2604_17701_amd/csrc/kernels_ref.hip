@@ -83,24 +83,37 @@ void launch_embed(Ctx *c, const Fwd &f) {
 // ------------------------------------------------------------------------------------------ RMSNorm
 // x[m] += y[0][m] + ... + y[n_partial-1][m] (fixed order), then out[m] = x[m] / sqrt(mean(x^2)+eps) * g
 template <typename WT, typename AT>
-__global__ void k_rmsnorm(float *x, const float *__restrict__ y, int n_partial, size_t partial_stride,
+__global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restrict__ y, int n_partial, size_t partial_stride,
                           const WT *__restrict__ g, int d, float eps, AT *out, float *out_f32) {
-    __shared__ float red[4];
+    __shared__ float red[16];
     const int m = blockIdx.x;
     float *xr = x + (size_t)m * d;
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float v = xr[i];
-        for (int p = 0; p < n_partial; ++p) v += y[p * partial_stride + (size_t)m * d + i];
-        if (n_partial) xr[i] = v;
-        ss += v * v;
+    // 1024 threads, four consecutive elements each per pass; the slices are loaded independently and
+    // added in slice order
+    for (int i = threadIdx.x * 4; i < d; i += 4096) {
+        float4 v = *reinterpret_cast<const float4 *>(xr + i);
+        float4 part[MAX_SPLITS];
+#pragma unroll
+        for (int p = 0; p < MAX_SPLITS; ++p)
+            if (p < n_partial) part[p] = *reinterpret_cast<const float4 *>(y + p * partial_stride + (size_t)m * d + i);
+#pragma unroll
+        for (int p = 0; p < MAX_SPLITS; ++p)
+            if (p < n_partial) { v.x += part[p].x; v.y += part[p].y; v.z += part[p].z; v.w += part[p].w; }
+        if (n_partial) *reinterpret_cast<float4 *>(xr + i) = v;
+        ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
-    ss = block_sum<256>(ss, red);
+    ss = block_sum<1024>(ss, red);
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float v = xr[i] * inv * Elem<WT>::load(g + i);
-        Elem<AT>::store(out + (size_t)m * d + i, v);
-        if (out_f32) out_f32[(size_t)m * d + i] = v;
+    for (int i = threadIdx.x * 4; i < d; i += 4096) {
+        const float4 v = *reinterpret_cast<const float4 *>(xr + i);
+        float4 r;
+        r.x = v.x * inv * Elem<WT>::load(g + i);
+        r.y = v.y * inv * Elem<WT>::load(g + i + 1);
+        r.z = v.z * inv * Elem<WT>::load(g + i + 2);
+        r.w = v.w * inv * Elem<WT>::load(g + i + 3);
+        *reinterpret_cast<float4 *>(out + (size_t)m * d + i) = r;
+        if (out_f32) *reinterpret_cast<float4 *>(out_f32 + (size_t)m * d + i) = r;
     }
 }
 
@@ -109,10 +122,10 @@ void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, void *out, f
     const int d = c->cfg.d_model;
     const size_t stride = (size_t)c->rows_max * d;
     if (c->bf16)
-        hipLaunchKernelGGL((k_rmsnorm<bf16_t, float>), dim3(rows), dim3(256), 0, c->stream, c->x, c->y, n_partial,
+        hipLaunchKernelGGL((k_rmsnorm<bf16_t, float>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
                            stride, (const bf16_t *)g, d, c->cfg.rms_eps, (float *)out, out_f32);
     else
-        hipLaunchKernelGGL((k_rmsnorm<float, float>), dim3(rows), dim3(256), 0, c->stream, c->x, c->y, n_partial,
+        hipLaunchKernelGGL((k_rmsnorm<float, float>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
                            stride, (const float *)g, d, c->cfg.rms_eps, (float *)out, out_f32);
 }
 
@@ -317,120 +330,6 @@ __global__ void k_argmax_rows(const float *__restrict__ z, int V, int32_t *amax)
 void launch_argmax(Ctx *c, int rows) {
     ProfScope ps(c, KC_ARGMAX);
     hipLaunchKernelGGL(k_argmax_rows, dim3(rows), dim3(256), 0, c->stream, c->logits, c->cfg.vocab, c->amax);
-}
-
-// ------------------------------------------------------------------------------------------ decision head
-// One block per drafted position.  z = [h^D ; h^T ; c] is never built: W1's row is walked in three
-// segments.  h^T and c are float; h^D and the head parameters have the storage type.
-template <typename WT>
-__global__ void k_head(const WT *__restrict__ w1, const WT *__restrict__ b1, const WT *__restrict__ w2,
-                       const WT *__restrict__ b2, int dD, int dT, int dC, int dJ, int act, const WT *__restrict__ hd,
-                       const int32_t *__restrict__ hd_row, int n_hd, const float *__restrict__ h_t,
-                       const float *__restrict__ csi, const int32_t *__restrict__ stream_ids,
-                       const int32_t *__restrict__ proto, const int32_t *__restrict__ tokens,
-                       const int32_t *__restrict__ amax, const int32_t *__restrict__ pred_next, int k, int max_batch,
-                       int gate_all, float *p_acc, int32_t *scored) {
-    __shared__ float red[4];
-    const int m = blockIdx.x, b = m / k, j = m - b * k, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int slot = min(max(stream_ids[b], 0), max_batch - 1);
-    const int t_pred = j == 0 ? pred_next[slot] : amax[m - 1];
-    const bool mismatch = tokens[m] != t_pred;
-    int hr = hd_row ? hd_row[m] : m;
-    if (hr >= n_hd) hr = -1;
-    const bool want = gate_all || proto[b] == WISV_PROTO_FH || mismatch;
-    if (!(want && hr >= 0)) {
-        if (tid == 0) { p_acc[m] = 1.0f; scored[m] = 0; }
-        return;
-    }
-    const int din = dD + dT + dC;
-    const WT *hdr = hd + (size_t)hr * dD;
-    const float *htr = h_t + (size_t)m * dT, *cr = csi + (size_t)b * dC;
-    float part = 0.f;
-    for (int r = wave; r < dJ; r += 4) {
-        const WT *wr = w1 + (size_t)r * din;
-        float acc = 0.f;
-        for (int i = lane; i < dD; i += 64) acc = fmaf(Elem<WT>::load(wr + i), Elem<WT>::load(hdr + i), acc);
-        for (int i = lane; i < dT; i += 64) acc = fmaf(Elem<WT>::load(wr + dD + i), htr[i], acc);
-        for (int i = lane; i < dC; i += 64) acc = fmaf(Elem<WT>::load(wr + dD + dT + i), cr[i], acc);
-        acc = wave_sum(acc) + Elem<WT>::load(b1 + r);
-        const float a = act == WISV_ACT_RELU ? fmaxf(acc, 0.f) : acc / (1.0f + expf(-acc));
-        part = fmaf(Elem<WT>::load(w2 + r), a, part);
-    }
-    if (lane == 0) red[wave] = part;
-    __syncthreads();
-    if (tid == 0) {
-        const float s = ((red[0] + red[1]) + (red[2] + red[3])) + Elem<WT>::load(b2);
-        p_acc[m] = 1.0f / (1.0f + expf(s));
-        scored[m] = 1;
-    }
-}
-
-// ------------------------------------------------------------------------------------------ localize + first reject
-// one thread per stream
-__global__ void k_decide(int batch, int k, int max_batch, const int32_t *__restrict__ stream_ids,
-                         const int32_t *__restrict__ tokens, const int32_t *__restrict__ amax,
-                         const float *__restrict__ p_acc, const int32_t *__restrict__ scored,
-                         const float *__restrict__ tau, int gate_all, int commit, int32_t *kv_len, int32_t *pred_next,
-                         int32_t *alen, int32_t *ytok, int32_t *targ, uint32_t *mask_out, uint32_t *status_out) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= batch) return;
-    const int slot = min(max(stream_ids[b], 0), max_batch - 1);
-    const int pn = pred_next[slot];
-    uint32_t mask = 0, status = 0;
-    int first = k;
-    for (int j = k - 1; j >= 0; --j) {
-        const int m = b * k + j;
-        const int t = j == 0 ? pn : amax[m - 1];
-        const bool mismatch = tokens[m] != t;
-        if (mismatch) mask |= 1u << j;
-        if (gate_all || mismatch) {
-            bool reject;
-            if (!scored[m]) { reject = true; status |= WISV_STATUS_MISSING_HIDDEN; }
-            else reject = !(p_acc[m] >= tau[b]);
-            if (reject) first = j;
-        }
-    }
-    const int y = first == 0 ? pn : amax[b * k + first - 1];
-    alen[b] = first;
-    ytok[b] = y;
-    if (targ) {
-        targ[b * (k + 1)] = pn;
-        for (int j = 0; j < k; ++j) targ[b * (k + 1) + j + 1] = amax[b * k + j];
-    }
-    if (mask_out) mask_out[b] = mask;
-    if (status_out) status_out[b] = status;
-    if (commit) {
-        kv_len[slot] += first;
-        pred_next[slot] = y;
-    }
-}
-
-void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in, const wisv_round_out &out) {
-    const wisv_config &g = c->cfg;
-    const int gate_all = (in.flags & WISV_FLAG_GATE_ALL) ? 1 : 0, commit = (in.flags & WISV_FLAG_NO_COMMIT) ? 0 : 1;
-    int32_t *scored = c->scored;
-    {
-        ProfScope ps(c, KC_HEAD);
-        if (c->bf16)
-            hipLaunchKernelGGL(k_head<bf16_t>, dim3(f.rows), dim3(256), 0, c->stream, (const bf16_t *)c->head_w1,
-                               (const bf16_t *)c->head_b1, (const bf16_t *)c->head_w2, (const bf16_t *)c->head_b2,
-                               g.d_draft, g.d_model, g.d_csi, g.d_head_hidden, g.head_act, (const bf16_t *)in.hd,
-                               in.hd_row, in.n_hd, c->h_t, in.csi, in.stream_ids, in.proto, in.draft_tokens, c->amax,
-                               c->d_pred_next, f.k, g.max_batch, gate_all, out.p_accept, scored);
-        else
-            hipLaunchKernelGGL(k_head<float>, dim3(f.rows), dim3(256), 0, c->stream, (const float *)c->head_w1,
-                               (const float *)c->head_b1, (const float *)c->head_w2, (const float *)c->head_b2,
-                               g.d_draft, g.d_model, g.d_csi, g.d_head_hidden, g.head_act, (const float *)in.hd,
-                               in.hd_row, in.n_hd, c->h_t, in.csi, in.stream_ids, in.proto, in.draft_tokens, c->amax,
-                               c->d_pred_next, f.k, g.max_batch, gate_all, out.p_accept, scored);
-    }
-    {
-        ProfScope ps(c, KC_DECIDE);
-        hipLaunchKernelGGL(k_decide, dim3((f.batch + 63) / 64), dim3(64), 0, c->stream, f.batch, f.k, g.max_batch,
-                           in.stream_ids, in.draft_tokens, c->amax, out.p_accept, scored, in.tau, gate_all, commit,
-                           c->d_kv_len, c->d_pred_next, out.accepted_len, out.correction_token, out.target_argmax,
-                           out.mismatch_mask, out.status);
-    }
 }
 
 // after a prefill chunk: the slot's length grows by the chunk, pred_next = greedy token of its last row

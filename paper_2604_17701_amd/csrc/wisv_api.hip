@@ -212,6 +212,18 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
                                   hipMemcpyDeviceToDevice, c->stream));
     }
 
+    // ---- decision head: W1 zero-padded to a multiple of 32 columns (the gathered z is padded alike)
+    {
+        const int din = g.d_draft + d + g.d_csi;
+        c->din_pad = (din + 31) / 32 * 32;
+        char *p;
+        CREATE_TRY(dalloc(c, &p, (size_t)g.d_head_hidden * c->din_pad * esz));
+        c->head_w1_pad = p;
+        launch_pad_cols(c, c->head_w1, p, g.d_head_hidden, din, c->din_pad);
+        CREATE_TRY(hipGetLastError());
+        c->head_w1_t = nullptr;
+    }
+
     // ---- re-tiled copies for the weight-streaming MFMA GEMM (bf16, every reduction length a multiple of 32)
     c->ws_ok = c->bf16 && d % 32 == 0 && c->d_q % 32 == 0 && F % 32 == 0;
     c->lm_head_t = nullptr;
@@ -226,6 +238,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
             return hipGetLastError();
         };
         CREATE_TRY(retile(&c->lm_head_t, c->lm_head, V, d, 0));
+        CREATE_TRY(retile(&c->head_w1_t, c->head_w1_pad, g.d_head_hidden, c->din_pad, 0));
         for (int l = 0; l < g.n_layers; ++l) {
             LayerW &L = c->layers[l];
             CREATE_TRY(retile(&L.wqkv_t, L.wqkv, c->d_qkv, d, 0));
@@ -301,6 +314,8 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     }
     CREATE_TRY(dalloc(c, &c->gu, (size_t)R * 2 * F));
     CREATE_TRY(dalloc(c, &c->h_t, (size_t)R * d));
+    CREATE_TRY(dalloc(c, &c->z, (size_t)R * c->din_pad));
+    CREATE_TRY(dalloc(c, &c->hu, (size_t)MAX_SPLITS * R * g.d_head_hidden));
     CREATE_TRY(dalloc(c, &c->a, (size_t)R * d));
     CREATE_TRY(dalloc(c, &c->q, (size_t)R * c->d_q));
     CREATE_TRY(dalloc(c, &c->o, (size_t)R * c->d_q));
@@ -352,8 +367,8 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             launch_attn_ref(c, f, l);
             ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
             launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
-            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, 2 * F, d, KC_GEMM)) {
-                launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM);
+            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, 2 * F, d, KC_GEMM_GATEUP)) {
+                launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
                 launch_swiglu(c, f.rows);
             }
             ny = product(L.wdown_t, L.wdown, c->h, c->y, ys, d, F);
@@ -374,7 +389,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         launch_attn_ref(c, f, l);
         launch_gemm_ref(c, c->o, L.wo, c->y, f.rows, d, c->d_q, KC_GEMM);
         launch_rmsnorm(c, f.rows, 1, L.ffn_norm, c->a, nullptr);                   // + attention update
-        launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM);
+        launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
         launch_swiglu(c, f.rows);
         launch_gemm_ref(c, c->h, L.wdown, c->y, f.rows, d, F, KC_GEMM);
     }
@@ -641,7 +656,7 @@ extern "C" int wisv_last_round_ms(wisv_ctx *ctx, float *ms) {
     return WISV_OK;
 }
 
-static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm", "rope_append", "attention",
+static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm_qkv_o_down", "gemm_gate_up", "rope_append", "attention",
                                             "swiglu", "lm_head", "argmax", "head", "decide"};
 
 extern "C" int wisv_profile_enable(wisv_ctx *ctx, int32_t on) {

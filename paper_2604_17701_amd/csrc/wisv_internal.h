@@ -46,7 +46,7 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
 enum KernelClass {
-    KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_ROPE, KC_ATTN, KC_SWIGLU, KC_LMHEAD, KC_ARGMAX,
+    KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_SWIGLU, KC_LMHEAD, KC_ARGMAX,
     KC_HEAD, KC_DECIDE, KC_COUNT
 };
 
@@ -68,6 +68,8 @@ struct Ctx {
     bool ws_ok;          // shapes allow the weight-streaming MFMA GEMM
     std::vector<LayerW> layers;
     void *head_w1, *head_b1, *head_w2, *head_b2;
+    void *head_w1_pad, *head_w1_t;   // W1 with its rows zero-padded to din_pad columns; its re-tiled copy (bf16)
+    int din_pad;                     // d_draft + d_model + d_csi rounded up to a multiple of 32
     float *rope_cos, *rope_sin;   // [max_ctx][head_dim/2]
 
     // KV cache [n_layers][max_batch][2][n_kv_heads][max_ctx][head_dim]
@@ -91,6 +93,7 @@ struct Ctx {
     int32_t *row_slot, *row_pos, *amax, *scored;
     float *x, *y, *qkv, *gu, *h_t, *logits;   // y and qkv hold up to MAX_SPLITS partial slices
     float *cand_val;
+    float *z, *hu;                // decision head: gathered inputs [rows][din_pad], first-layer slices
     int32_t *cand_idx;
     float *a, *q, *o, *h;         // activations handed to the matrix products (float in both paths)
     size_t logits_rows;
@@ -131,6 +134,7 @@ void launch_swiglu(Ctx *c, int rows);
 void launch_argmax(Ctx *c, int rows);
 void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in_dev, const wisv_round_out &out_dev);
 void launch_set_pred_next(Ctx *c, int slot, int row, int new_len);
+void launch_pad_cols(Ctx *c, const void *src, void *dst, int rows, int cols, int cols_pad);
 
 // ---------------------------------------------------------------- weight-streaming GEMM (kernels_gemm.hip)
 constexpr int MAX_SPLITS = 8;
