@@ -3,11 +3,16 @@
 //
 // Y[m, n] = sum_k X[m, k] W[n, k] is computed "swapped": the 16x16x32 MFMA takes a 16-row block of W as
 // its A operand and 16 activation rows as its B operand, so the output-feature dimension fills the
-// matrix core however few rows there are.  Activations arrive as float and are fed as two bf16 terms
-// (x = hi + lo), one MFMA each: the products are then exact to about 2^-17 while the weights stay bf16;
-// the second MFMA costs issue slots this memory-bound kernel has to spare.  W is stored re-tiled: tile (rb, kt) holds W[16rb..+16][32kt..+32]
+// matrix core however few rows there are.  W is stored re-tiled: tile (rb, kt) holds W[16rb..+16][32kt..+32]
 // as 64 lanes x 8 bf16 in exactly the order the MFMA wants, so that one wave-wide 16-byte load fetches a
-// contiguous KiB and a wave walking along k reads one contiguous stream.
+// contiguous KiB and a wave walking along k reads one contiguous stream.  Activations arrive as two bf16
+// planes (x = hi + lo, written by whichever kernel produced them), one MFMA each: the products are then
+// exact to about 2^-17 while the weights stay bf16; the second MFMA costs issue slots this memory-bound
+// kernel has to spare.
+//
+// A workgroup is WR x WK waves: WR groups of RB row-blocks, and WK slices of the workgroup's k-range whose
+// accumulators are added through LDS in slice order.  Small matrices need the k-slicing to put enough
+// waves in flight to pull HBM bandwidth; the grid's y dimension splits k further into partial outputs.
 #include <algorithm>
 
 #include "wisv_internal.h"
@@ -45,44 +50,49 @@ void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, voi
                        n_rows, kd, nrb, nkt, pair_rows, (uint4 *)out);
 }
 
+// row-blocks are padded to a multiple of 8 so that a workgroup may own 1, 2, 4 or 8 of them
+int ws_padded_row_blocks(int n_rows) { return ((n_rows + 15) / 16 + 7) / 8 * 8; }
+
 // ------------------------------------------------------------------------------------------ the GEMM
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
 
 struct GemmArgs {
-    const u32x4 *Wt;      // re-tiled weights [nrb][nkt][64]
-    const float *X;       // activations [M][kd], float: split into two bf16 terms while staged
+    const u32x4 *Wt;           // re-tiled weights [nrb][nkt][64]
+    const bf16_t *Xhi, *Xlo;   // activation planes [M][kd]
     int M, N, kd, nrb, nkt, kt_per_split;
-    int kc;               // k-tiles of X staged in LDS at a time (a multiple of the prefetch depth)
-    float *Yp;            // EPI_PARTIAL: [S][m_stride][N];  EPI_ARGMAX with logits != null: [M][N]
-    size_t split_stride;  // elements between consecutive split slices of Yp
-    float *H;             // EPI_SWIGLU: [M][N/2]
-    float *cand_val;      // EPI_ARGMAX: [M][n_cand]
+    int kcw;                   // k-tiles per wave staged in LDS at a time (a multiple of the prefetch depth)
+    float *Yp;                 // EPI_PARTIAL: [S][split_stride];  EPI_ARGMAX with logits != null: [M][N]
+    size_t split_stride;
+    ActBuf H;                  // EPI_SWIGLU: [M][N/2] float + planes
+    float *cand_val;           // EPI_ARGMAX: [M][n_cand]
     int32_t *cand_idx;
     int n_cand;
 };
 
-// NT: 16-row activation tiles held per wave; RB: row-blocks of W per wave; U: depth of the register prefetch.
-// X is staged through LDS in chunks of g.kc k-tiles (double-buffered when there is more than one chunk).
-template <int NT, int RB, int U, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
+// NT: 16-row activation tiles per wave; RB: row-blocks per wave; WR x WK waves per workgroup; U: prefetch depth
+template <int NT, int RB, int WR, int WK, int U, int EPI>
+__global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NTH = 64 * WR * WK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave / WK, wk = wave % WK;
     const int kt0 = blockIdx.y * g.kt_per_split;
     const int ntile = min(g.kt_per_split, g.nkt - kt0);
-    const int rb0 = (blockIdx.x * 4 + wave) * RB;
-    const bool active = rb0 < g.nrb;   // RB divides nrb by construction of the launch
+    const int sub = (ntile + WK - 1) / WK;                         // k-tiles per wave
+    const int my0 = wk * sub, myn = max(0, min(sub, ntile - my0));
+    const int rb0 = (blockIdx.x * WR + wr) * RB;
+    const bool active = rb0 < g.nrb;                               // RB * WR divides nrb (padded)
 
     // ---- start the weight stream before anything else: it does not depend on the activations
     const u32x4 *wp[RB];
     u32x4 abuf[U][RB];
 #pragma unroll
-    for (int r = 0; r < RB; ++r) wp[r] = g.Wt + ((size_t)(active ? rb0 + r : 0) * g.nkt + kt0) * 64 + lane;
+    for (int r = 0; r < RB; ++r) wp[r] = g.Wt + ((size_t)(active ? rb0 + r : 0) * g.nkt + kt0 + my0) * 64 + lane;
     if (active) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int r = 0; r < RB; ++r)
-                if (u < ntile) abuf[u][r] = __builtin_nontemporal_load(wp[r] + (size_t)u * 64);
+                if (u < myn) abuf[u][r] = __builtin_nontemporal_load(wp[r] + (size_t)u * 64);
     }
 
     floatx4 acc[RB][NT];
@@ -91,30 +101,23 @@ __global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // ---- X chunk c (k-tiles [c kc, (c+1) kc) of this split) lives at lds + (c & 1) * buf_bytes as two
-    //      bf16 planes: hi = bf16(x) at row m * pitch, lo = bf16(x - hi) at lo_off + m * pitch
-    //      (x = hi + lo to 2^-17 relative); pitch = chunk bytes + 16 spreads rows over the banks
-    const int kc = g.kc, pitch = kc * 64 + 16, lo_off = g.M * pitch, buf_bytes = 2 * lo_off;
-    const int nchunk = (ntile + kc - 1) / kc;
+    // ---- activations: chunk ch holds, for every k-slice w, its tiles [ch kcw, (ch+1) kcw) as
+    //      lds[ch & 1][plane][w][m][kcw * 64 + 16 bytes]; the 16 spreads rows over the banks
+    const int kcw = g.kcw, pitch = kcw * 64 + 16, wk_bytes = g.M * pitch, plane_bytes = WK * wk_bytes,
+              buf_bytes = 2 * plane_bytes;
+    const int nchunk = (sub + kcw - 1) / kcw;
     auto stage = [&](int ch) {
         unsigned char *dst = lds + (size_t)(ch & 1) * buf_bytes;
-        const int tiles = min(kc, ntile - ch * kc), vec_per_row = tiles * 4;
-        const float *src = g.X + (size_t)(kt0 + ch * kc) * 32;
-        for (int i = tid; i < g.M * vec_per_row; i += 256) {
-            const int m = i / vec_per_row, v = i - m * vec_per_row;
-            const float4 x0 = *reinterpret_cast<const float4 *>(src + (size_t)m * g.kd + v * 8);
-            const float4 x1 = *reinterpret_cast<const float4 *>(src + (size_t)m * g.kd + v * 8 + 4);
-            const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bf16_t h0 = f32_to_bf16(xs[2 * e]), h1 = f32_to_bf16(xs[2 * e + 1]);
-                const bf16_t l0 = f32_to_bf16(xs[2 * e] - bf16_to_f32(h0)), l1 = f32_to_bf16(xs[2 * e + 1] - bf16_to_f32(h1));
-                hi[e] = h0 | ((uint32_t)h1 << 16);
-                lo[e] = l0 | ((uint32_t)l1 << 16);
+        const int vec_per_row = kcw * 4, per_wk = g.M * vec_per_row;
+        for (int i = tid; i < WK * per_wk; i += NTH) {
+            const int w = i / per_wk, rem = i - w * per_wk, m = rem / vec_per_row, v = rem - m * vec_per_row;
+            const int lt = ch * kcw + (v >> 2), kt = w * sub + lt;          // tile within the slice / the workgroup range
+            if (lt < sub && kt < ntile) {
+                const size_t off = (size_t)m * g.kd + (size_t)(kt0 + kt) * 32 + (v & 3) * 8;
+                unsigned char *d = dst + (size_t)w * wk_bytes + (size_t)m * pitch + v * 16;
+                *reinterpret_cast<uint4 *>(d) = *reinterpret_cast<const uint4 *>(g.Xhi + off);
+                *reinterpret_cast<uint4 *>(d + plane_bytes) = *reinterpret_cast<const uint4 *>(g.Xlo + off);
             }
-            *reinterpret_cast<uint4 *>(dst + (size_t)m * pitch + v * 16) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-            *reinterpret_cast<uint4 *>(dst + lo_off + (size_t)m * pitch + v * 16) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
         }
     };
     const int bj = lane & 15, bg = lane >> 4;
@@ -123,9 +126,9 @@ __global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
         __syncthreads();   // chunk ch is staged; everyone is done with the buffer chunk ch + 1 goes to
         if (ch + 1 < nchunk) stage(ch + 1);
         if (!active) continue;
-        const unsigned char *buf = lds + (size_t)(ch & 1) * buf_bytes;
-        const int kend = min(ntile, (ch + 1) * kc);
-        for (int kt = ch * kc; kt < kend; kt += U) {
+        const unsigned char *buf = lds + (size_t)(ch & 1) * buf_bytes + (size_t)wk * wk_bytes;
+        const int kend = min(myn, (ch + 1) * kcw);
+        for (int kt = ch * kcw; kt < kend; kt += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (kt + u < kend) {
@@ -133,17 +136,16 @@ __global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
 #pragma unroll
                     for (int r = 0; r < RB; ++r) {
                         a[r] = abuf[u][r];
-                        if (kt + u + U < ntile)
-                            abuf[u][r] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u + U) * 64);
+                        if (kt + u + U < myn) abuf[u][r] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u + U) * 64);
                     }
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         const int m = t * 16 + bj;
                         uint4 bh = make_uint4(0, 0, 0, 0), bl = bh;
                         if (m < g.M) {
-                            const unsigned char *p = buf + (size_t)m * pitch + ((kt + u - ch * kc) * 32 + bg * 8) * 2;
+                            const unsigned char *p = buf + (size_t)m * pitch + ((kt + u - ch * kcw) * 32 + bg * 8) * 2;
                             bh = *reinterpret_cast<const uint4 *>(p);
-                            bl = *reinterpret_cast<const uint4 *>(p + lo_off);
+                            bl = *reinterpret_cast<const uint4 *>(p + plane_bytes);
                         }
 #pragma unroll
                         for (int r = 0; r < RB; ++r) {
@@ -157,7 +159,28 @@ __global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
             }
         }
     }
-    if (!active) return;
+
+    // ---- add the WK k-slices of each row-block group through LDS, in slice order
+    if (WK > 1) {
+        __syncthreads();
+        floatx4 *red = reinterpret_cast<floatx4 *>(lds);
+        if (wk > 0 && active) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    red[(((size_t)(wr * (WK - 1) + wk - 1) * RB + r) * NT + t) * 64 + lane] = acc[r][t];
+        }
+        __syncthreads();
+        if (wk > 0 || !active) return;
+        for (int s = 1; s < WK; ++s)
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[r][t] += red[(((size_t)(wr * (WK - 1) + s - 1) * RB + r) * NT + t) * 64 + lane];
+    } else if (!active) {
+        return;
+    }
 
     // ---- epilogue.  acc[r][t][e] = Y[m = 16 t + lane % 16][n = 16 (rb0 + r) + 4 (lane / 16) + e]
     if (EPI == EPI_PARTIAL) {
@@ -183,18 +206,12 @@ __global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
             const int m = t * 16 + bj;
             if (m >= g.M) continue;
 #pragma unroll
-            for (int pr = 0; pr < RB / 2; ++pr) {
+            for (int pr = 0; pr < (RB + 1) / 2; ++pr) {
                 const int f = ((rb0 >> 1) + pr) * 16 + bg * 4;
-                floatx4 hv;
-#pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float gt = acc[2 * pr][t][e], up = acc[2 * pr + (RB > 1 ? 1 : 0)][t][e];
-                    hv[e] = gt / (1.0f + expf(-gt)) * up;
+                    if (f + e < F) act_store(g.H, (size_t)m * F + f + e, gt / (1.0f + expf(-gt)) * up);
                 }
-                if (f + 3 < F && (F & 3) == 0) *reinterpret_cast<floatx4 *>(g.H + (size_t)m * F + f) = hv;
-                else
-                    for (int e = 0; e < 4; ++e)
-                        if (f + e < F) g.H[(size_t)m * F + f + e] = hv[e];
             }
         }
     } else {   // EPI_ARGMAX: best (value, lowest index) of this wave's 16*RB features for every row
@@ -221,7 +238,7 @@ __global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
                 if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
             }
             if (bg == 0 && m < g.M) {
-                const int slot = blockIdx.x * 4 + wave;   // one slot per wave
+                const int slot = blockIdx.x * WR + wr;   // one slot per row-block group
                 g.cand_val[(size_t)m * g.n_cand + slot] = best;
                 g.cand_idx[(size_t)m * g.n_cand + slot] = idx;
             }
@@ -229,7 +246,7 @@ __global__ __launch_bounds__(256) void k_gemm_ws(GemmArgs g) {
     }
 }
 
-// final argmax over the per-wave candidates of every row
+// final argmax over the per-group candidates of every row
 __global__ void k_argmax_cand(const float *__restrict__ val, const int32_t *__restrict__ idxs, int n_cand, int stride,
                               int32_t *amax) {
     __shared__ float bv[4];
@@ -257,119 +274,126 @@ __global__ void k_argmax_cand(const float *__restrict__ val, const int32_t *__re
     }
 }
 
-// LDS bytes of the X staging (hi and lo planes) for a chunk of kc k-tiles (two buffers unless one chunk
-// covers the split)
-static size_t ws_lds(int M, int kc, int ntile) { return (size_t)(ntile > kc ? 2 : 1) * 2 * M * (kc * 64 + 16); }
-
-// largest chunk (a multiple of the prefetch depth U) whose staging fits the LDS budget; 0 if none does
-static int pick_kc(int M, int ntile, int U, size_t budget) {
-    int kc = (ntile + U - 1) / U * U;
-    while (kc > U && ws_lds(M, kc, ntile) > budget) kc = (kc / 2 + U - 1) / U * U;
-    return ws_lds(M, kc, ntile) <= budget ? kc : 0;
+// ------------------------------------------------------------------------------------------ launch
+// LDS bytes: activation chunk (two planes, WK slices; two buffers when a slice needs several chunks),
+// or the slice-reduction scratch if that is larger
+static size_t ws_lds(int M, int kcw, int sub, int NT, int RB, int WR, int WK) {
+    const size_t x = (size_t)(sub > kcw ? 2 : 1) * 2 * WK * M * (kcw * 64 + 16);
+    const size_t red = (size_t)WR * (WK - 1) * RB * NT * 1024;
+    return std::max(x, red);
 }
 
-// row-blocks are padded to a multiple of 4 so that a wave may own 1, 2 or 4 of them
-int ws_padded_row_blocks(int n_rows) { return ((n_rows + 15) / 16 + 3) / 4 * 4; }
-
-template <int NT, int RB, int EPI> static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits) {
-    constexpr int U = RB == 1 ? 8 : (RB == 2 ? 4 : 2);
-    // small row counts stay within the default 64 KiB of dynamic LDS; more rows opt in to the CU's 160 KiB
-    const size_t budget = NT <= 2 ? 60 * 1024 : 144 * 1024;
-    g.kc = pick_kc(g.M, g.kt_per_split, U, budget);
-    if (!g.kc) return false;
-    const size_t lds = ws_lds(g.M, g.kc, g.kt_per_split);
+template <int NT, int RB, int WR, int WK, int U, int EPI>
+static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
+    const int sub = (g.kt_per_split + WK - 1) / WK;
+    // largest chunk (a multiple of U) within the soft budget, else within what a CU has
+    int kcw = (sub + U - 1) / U * U;
+    for (size_t budget : {soft_budget, (size_t)150 * 1024}) {
+        kcw = (sub + U - 1) / U * U;
+        while (kcw > U && ws_lds(g.M, kcw, sub, NT, RB, WR, WK) > budget) kcw = (kcw / 2 + U - 1) / U * U;
+        if (ws_lds(g.M, kcw, sub, NT, RB, WR, WK) <= budget) break;
+    }
+    const size_t lds = ws_lds(g.M, kcw, sub, NT, RB, WR, WK);
+    if (lds > 150 * 1024) return false;
+    g.kcw = kcw;
     static bool opted_in = false;     // per instantiation
     if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<NT, RB, U, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<NT, RB, WR, WK, U, EPI>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return false;
         opted_in = true;
     }
-    const int waves = g.nrb / RB;
-    dim3 grid((waves + 3) / 4, splits);
-    hipLaunchKernelGGL((k_gemm_ws<NT, RB, U, EPI>), grid, dim3(256), lds, c->stream, g);
+    dim3 grid((g.nrb / RB + WR - 1) / WR, splits);
+    hipLaunchKernelGGL((k_gemm_ws<NT, RB, WR, WK, U, EPI>), grid, dim3(64 * WR * WK), lds, c->stream, g);
     return true;
-}
-
-// few rows: one row-block per wave and a deep prefetch; many rows: more row-blocks per wave so that one
-// LDS read of the activations serves several weight tiles
-template <int EPI> static bool launch_ws_nt(Ctx *c, GemmArgs &g, int splits) {
-    const int nt = (g.M + 15) / 16;
-    constexpr int RS = EPI == EPI_SWIGLU ? 2 : 1;   // SwiGLU needs gate and up in the same wave
-    switch (nt) {
-        case 1: return launch_ws_t<1, RS, EPI>(c, g, splits);
-        case 2: return launch_ws_t<2, 2, EPI>(c, g, splits);
-        case 3: return launch_ws_t<3, 2, EPI>(c, g, splits);
-        case 4: return launch_ws_t<4, 4, EPI>(c, g, splits);
-        case 5: return launch_ws_t<5, 4, EPI>(c, g, splits);
-        case 6: return launch_ws_t<6, 4, EPI>(c, g, splits);
-        default: return false;
-    }
-}
-
-static int rb_per_wave(int M, int epi) {
-    const int nt = (M + 15) / 16;
-    return nt == 1 ? (epi == EPI_SWIGLU ? 2 : 1) : (nt <= 3 ? 2 : 4);
-}
-
-// Number of k-splits: enough waves to keep every CU streaming, at least 8 k-tiles per split, and no
-// more slices than the partial buffer holds.
-static int pick_splits(int M, int nkt, int waves_per_split, int max_splits) {
-    const int want_waves = M <= 16 ? 2048 : 1024;
-    int s = (want_waves + waves_per_split - 1) / waves_per_split;
-    s = std::min(s, std::min(max_splits, std::max(1, nkt / 8)));
-    return std::max(s, 1);
 }
 
 bool ws_supported(const Ctx *c, int rows, int kd) {
     return c->bf16 && kd % 32 == 0 && rows <= 96;
 }
 
-static void fill_args(GemmArgs &g, const void *Wt, const void *X, int rows, int n, int kd) {
+static void fill_args(GemmArgs &g, const void *Wt, const ActBuf &X, int rows, int n, int kd) {
     g.Wt = (const u32x4 *)Wt;
-    g.X = (const float *)X;
+    g.Xhi = X.hi; g.Xlo = X.lo;
     g.M = rows; g.N = n; g.kd = kd;
     g.nrb = ws_padded_row_blocks(n); g.nkt = kd / 32;
 }
 
 // Y partial slices: returns the number of slices written to `Yp` ([S][split_stride]), 0 if the shape cannot
 // be served (nothing was launched)
-int launch_gemm_ws_partial(Ctx *c, const void *Wt, const void *X, float *Yp, size_t split_stride, int max_splits,
+int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
                            int rows, int n, int kd, int kclass) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
     fill_args(g, Wt, X, rows, n, kd);
     g.Yp = Yp; g.split_stride = split_stride;
-    const int s = pick_splits(rows, g.nkt, g.nrb / rb_per_wave(rows, EPI_PARTIAL), max_splits);
+    const int nt = (rows + 15) / 16;
+    // splits: about 8192 waves in all for up to 16 rows (2 x 4 waves per workgroup), 2048 beyond; a wave keeps
+    // at least 4 k-tiles
+    const int wk = nt == 1 ? 4 : 1, rb = nt == 1 ? 1 : (nt <= 3 ? 2 : 4);
+    const int want = nt == 1 ? 8192 : 2048;
+    int s = (want + (g.nrb / rb) * wk - 1) / ((g.nrb / rb) * wk);
+    s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / (4 * wk)))));
     g.kt_per_split = (g.nkt + s - 1) / s;
     const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
-    return launch_ws_nt<EPI_PARTIAL>(c, g, splits) ? splits : 0;
+    bool ok;
+    switch (nt) {
+        case 1: ok = launch_ws_t<1, 1, 2, 4, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024); break;
+        case 2: ok = launch_ws_t<2, 2, 4, 1, 4, EPI_PARTIAL>(c, g, splits, 60 * 1024); break;
+        case 3: ok = launch_ws_t<3, 2, 4, 1, 4, EPI_PARTIAL>(c, g, splits, 60 * 1024); break;
+        case 4: ok = launch_ws_t<4, 4, 2, 1, 2, EPI_PARTIAL>(c, g, splits, 72 * 1024); break;
+        case 5: ok = launch_ws_t<5, 4, 2, 1, 2, EPI_PARTIAL>(c, g, splits, 72 * 1024); break;
+        case 6: ok = launch_ws_t<6, 4, 2, 1, 2, EPI_PARTIAL>(c, g, splits, 72 * 1024); break;
+        default: ok = false;
+    }
+    return ok ? splits : 0;
 }
 
 // gate/up with the SwiGLU fused (single split): H[rows][F] = silu(gate) * up.  The re-tiled matrix
 // alternates gate and up row-blocks, 2 * padded(F) in all.
-bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const void *X, void *H, int rows, int two_f, int kd, int kclass) {
+bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int two_f, int kd,
+                           int kclass) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
     fill_args(g, Wt, X, rows, two_f, kd);
     g.nrb = 2 * ws_padded_row_blocks(two_f / 2);
     g.kt_per_split = g.nkt;
-    g.H = (float *)H;
-    return launch_ws_nt<EPI_SWIGLU>(c, g, 1);
+    g.H = H;
+    switch ((rows + 15) / 16) {
+        // few rows: the whole activation slice sits in LDS, four long-lived waves per workgroup
+        case 1: return launch_ws_t<1, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 140 * 1024);
+        case 2: return launch_ws_t<2, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 72 * 1024);
+        case 3: return launch_ws_t<3, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 72 * 1024);
+        case 4: return launch_ws_t<4, 4, 2, 1, 2, EPI_SWIGLU>(c, g, 1, 72 * 1024);
+        case 5: return launch_ws_t<5, 4, 2, 1, 2, EPI_SWIGLU>(c, g, 1, 72 * 1024);
+        case 6: return launch_ws_t<6, 4, 2, 1, 2, EPI_SWIGLU>(c, g, 1, 72 * 1024);
+        default: return false;
+    }
 }
 
 // LM head with the argmax fused: greedy token of every row in c->amax; logits kept only on request
-bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const void *X, float *logits, int rows, int n, int kd, int kclass) {
+bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass) {
     GemmArgs g{};
     fill_args(g, Wt, X, rows, n, kd);
     g.kt_per_split = g.nkt;
     g.Yp = logits;
     g.cand_val = c->cand_val; g.cand_idx = c->cand_idx;
     g.n_cand = g.nrb;                     // at most one candidate slot per row-block
-    const int slots = g.nrb / rb_per_wave(rows, EPI_ARGMAX);
+    const int nt = (rows + 15) / 16;
+    const int slots = g.nrb / (nt == 1 ? 1 : (nt <= 3 ? 2 : 4));
     {
         ProfScope ps(c, kclass);
-        if (!launch_ws_nt<EPI_ARGMAX>(c, g, 1)) return false;
+        bool ok;
+        switch (nt) {
+            case 1: ok = launch_ws_t<1, 1, 8, 1, 4, EPI_ARGMAX>(c, g, 1, 36 * 1024); break;
+            case 2: ok = launch_ws_t<2, 2, 4, 1, 4, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
+            case 3: ok = launch_ws_t<3, 2, 4, 1, 4, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
+            case 4: ok = launch_ws_t<4, 4, 2, 1, 2, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
+            case 5: ok = launch_ws_t<5, 4, 2, 1, 2, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
+            case 6: ok = launch_ws_t<6, 4, 2, 1, 2, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
+            default: ok = false;
+        }
+        if (!ok) return false;
     }
     {
         ProfScope ps(c, KC_ARGMAX);

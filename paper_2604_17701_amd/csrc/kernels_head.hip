@@ -35,7 +35,7 @@ __global__ void k_head_concat(int dD, int dT, int dC, int din_pad, const WT *__r
                               const float *__restrict__ csi, const int32_t *__restrict__ stream_ids,
                               const int32_t *__restrict__ proto, const int32_t *__restrict__ tokens,
                               const int32_t *__restrict__ amax, const int32_t *__restrict__ pred_next, int k,
-                              int max_batch, int gate_all, float *z, int32_t *scored) {
+                              int max_batch, int gate_all, ActBuf z, int32_t *scored) {
     const int m = blockIdx.x, b = m / k, j = m - b * k, tid = threadIdx.x;
     const int slot = min(max(stream_ids[b], 0), max_batch - 1);
     const int t_pred = j == 0 ? pred_next[slot] : amax[m - 1];   // the target's greedy token for position j
@@ -45,15 +45,16 @@ __global__ void k_head_concat(int dD, int dT, int dC, int din_pad, const WT *__r
     const bool want = gate_all || proto[b] == WISV_PROTO_FH || mismatch;
     const bool sc = want && hr >= 0;
     if (tid == 0) scored[m] = sc ? 1 : 0;
-    float *zr = z + (size_t)m * din_pad;
+    const size_t z0 = (size_t)m * din_pad;
     if (!sc) {
-        for (int i = tid; i < din_pad; i += blockDim.x) zr[i] = 0.f;
+        for (int i = tid; i < din_pad; i += blockDim.x) act_store(z, z0 + i, 0.f);
         return;
     }
     const WT *hdr = hd + (size_t)hr * dD;
-    for (int i = tid; i < dD; i += blockDim.x) zr[i] = Elem<WT>::load(hdr + i);
-    for (int i = tid; i < dT; i += blockDim.x) zr[dD + i] = h_t[(size_t)m * dT + i];
-    for (int i = tid; i < din_pad - dD - dT; i += blockDim.x) zr[dD + dT + i] = i < dC ? csi[(size_t)b * dC + i] : 0.f;
+    for (int i = tid; i < dD; i += blockDim.x) act_store(z, z0 + i, Elem<WT>::load(hdr + i));
+    for (int i = tid; i < dT; i += blockDim.x) act_store(z, z0 + dD + i, h_t[(size_t)m * dT + i]);
+    for (int i = tid; i < din_pad - dD - dT; i += blockDim.x)
+        act_store(z, z0 + dD + dT + i, i < dC ? csi[(size_t)b * dC + i] : 0.f);
 }
 
 // one block per position: u = sum of the product's slices (fixed order), then the second layer
@@ -144,7 +145,8 @@ void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in, const wis
     if (streamed) {
         for (int r0 = 0; r0 < f.rows && streamed; r0 += 96) {
             const int rows = std::min(96, f.rows - r0);
-            const int ns = launch_gemm_ws_partial(c, c->head_w1_t, c->z + (size_t)r0 * din_pad, c->hu + (size_t)r0 * dJ,
+            const ActBuf zt{c->z.f + (size_t)r0 * din_pad, c->z.hi + (size_t)r0 * din_pad, c->z.lo + (size_t)r0 * din_pad};
+            const int ns = launch_gemm_ws_partial(c, c->head_w1_t, zt, c->hu + (size_t)r0 * dJ,
                                                   ustride, r0 == 0 ? MAX_SPLITS : n_partial, rows, dJ, din_pad, KC_HEAD);
             if (!ns || (r0 > 0 && ns != n_partial)) streamed = false;
             else n_partial = ns;
@@ -152,7 +154,7 @@ void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in, const wis
     }
     if (!streamed) {
         n_partial = 1;
-        launch_gemm_ref(c, c->z, c->head_w1_pad, c->hu, f.rows, dJ, din_pad, KC_HEAD);
+        launch_gemm_ref(c, c->z.f, c->head_w1_pad, c->hu, f.rows, dJ, din_pad, KC_HEAD);
     }
     {
         ProfScope ps(c, KC_HEAD);

@@ -84,7 +84,7 @@ void launch_embed(Ctx *c, const Fwd &f) {
 // x[m] += y[0][m] + ... + y[n_partial-1][m] (fixed order), then out[m] = x[m] / sqrt(mean(x^2)+eps) * g
 template <typename WT, typename AT>
 __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restrict__ y, int n_partial, size_t partial_stride,
-                          const WT *__restrict__ g, int d, float eps, AT *out, float *out_f32) {
+                          const WT *__restrict__ g, int d, float eps, ActBuf out, float *out_f32) {
     __shared__ float red[16];
     const int m = blockIdx.x;
     float *xr = x + (size_t)m * d;
@@ -112,21 +112,28 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restr
         r.y = v.y * inv * Elem<WT>::load(g + i + 1);
         r.z = v.z * inv * Elem<WT>::load(g + i + 2);
         r.w = v.w * inv * Elem<WT>::load(g + i + 3);
-        *reinterpret_cast<float4 *>(out + (size_t)m * d + i) = r;
+        *reinterpret_cast<float4 *>(out.f + (size_t)m * d + i) = r;
+        bf16_t h[4], l[4];
+        split2(r.x, h[0], l[0]);
+        split2(r.y, h[1], l[1]);
+        split2(r.z, h[2], l[2]);
+        split2(r.w, h[3], l[3]);
+        *reinterpret_cast<uint2 *>(out.hi + (size_t)m * d + i) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+        *reinterpret_cast<uint2 *>(out.lo + (size_t)m * d + i) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
         if (out_f32) *reinterpret_cast<float4 *>(out_f32 + (size_t)m * d + i) = r;
     }
 }
 
-void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, void *out, float *out_f32) {
+void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, const ActBuf &out, float *out_f32) {
     ProfScope ps(c, KC_NORM);
     const int d = c->cfg.d_model;
     const size_t stride = (size_t)c->rows_max * d;
     if (c->bf16)
         hipLaunchKernelGGL((k_rmsnorm<bf16_t, float>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
-                           stride, (const bf16_t *)g, d, c->cfg.rms_eps, (float *)out, out_f32);
+                           stride, (const bf16_t *)g, d, c->cfg.rms_eps, out, out_f32);
     else
         hipLaunchKernelGGL((k_rmsnorm<float, float>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
-                           stride, (const float *)g, d, c->cfg.rms_eps, (float *)out, out_f32);
+                           stride, (const float *)g, d, c->cfg.rms_eps, out, out_f32);
 }
 
 // ------------------------------------------------------------------------------------------ GEMM (fallback)
@@ -159,15 +166,15 @@ __global__ void k_gemm_ref(const AT *__restrict__ A, const WT *__restrict__ W, f
     }
 }
 
-void launch_gemm_ref(Ctx *c, const void *A, const void *W, float *Y, int rows, int n, int kd, int kclass) {
+void launch_gemm_ref(Ctx *c, const float *A, const void *W, float *Y, int rows, int n, int kd, int kclass) {
     ProfScope ps(c, kclass);
     constexpr int MT = 8;
     dim3 grid((n + 3) / 4, (rows + MT - 1) / MT);
     if (c->bf16)
-        hipLaunchKernelGGL((k_gemm_ref<bf16_t, float, MT>), grid, dim3(256), 0, c->stream, (const float *)A,
+        hipLaunchKernelGGL((k_gemm_ref<bf16_t, float, MT>), grid, dim3(256), 0, c->stream, A,
                            (const bf16_t *)W, Y, rows, n, kd);
     else
-        hipLaunchKernelGGL((k_gemm_ref<float, float, MT>), grid, dim3(256), 0, c->stream, (const float *)A,
+        hipLaunchKernelGGL((k_gemm_ref<float, float, MT>), grid, dim3(256), 0, c->stream, A,
                            (const float *)W, Y, rows, n, kd);
 }
 
@@ -224,7 +231,7 @@ void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial) {
 template <typename WT, typename AT>
 __global__ void k_attn_ref(const AT *__restrict__ q, const WT *__restrict__ kv_layer, size_t slot_stride, int H, int G,
                            int hd, int max_ctx, const int32_t *__restrict__ row_slot,
-                           const int32_t *__restrict__ row_pos, AT *o) {
+                           const int32_t *__restrict__ row_pos, ActBuf o) {
     extern __shared__ float smem[];
     float *qs = smem;            // [hd]
     float *red = smem + hd;      // [256 + 4]
@@ -263,7 +270,7 @@ __global__ void k_attn_ref(const AT *__restrict__ q, const WT *__restrict__ kv_l
     __syncthreads();
     if (part == 0) {
         for (int p = 1; p < nparts; ++p) acc += red[p * hd + dim];
-        Elem<AT>::store(o + (size_t)m * H * hd + (size_t)h * hd + dim, acc / sum);
+        act_store(o, (size_t)m * H * hd + (size_t)h * hd + dim, acc / sum);
     }
 }
 
@@ -285,19 +292,19 @@ void launch_attn_ref(Ctx *c, const Fwd &f, int layer) {
 }
 
 // ------------------------------------------------------------------------------------------ SwiGLU
-template <typename AT> __global__ void k_swiglu(const float *__restrict__ gu, int F, AT *h) {
+__global__ void k_swiglu(const float *__restrict__ gu, int F, ActBuf h) {
     const int m = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= F) return;
     const float g = gu[(size_t)m * 2 * F + i], u = gu[(size_t)m * 2 * F + F + i];
-    Elem<AT>::store(h + (size_t)m * F + i, g / (1.0f + expf(-g)) * u);
+    act_store(h, (size_t)m * F + i, g / (1.0f + expf(-g)) * u);
 }
 
 void launch_swiglu(Ctx *c, int rows) {
     ProfScope ps(c, KC_SWIGLU);
     const int F = c->cfg.d_ff;
     dim3 grid((F + 255) / 256, rows);
-    hipLaunchKernelGGL(k_swiglu<float>, grid, dim3(256), 0, c->stream, c->gu, F, c->h);
+    hipLaunchKernelGGL(k_swiglu, grid, dim3(256), 0, c->stream, c->gu, F, c->h);
 }
 
 // ------------------------------------------------------------------------------------------ argmax over logits rows

@@ -314,12 +314,26 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     }
     CREATE_TRY(dalloc(c, &c->gu, (size_t)R * 2 * F));
     CREATE_TRY(dalloc(c, &c->h_t, (size_t)R * d));
-    CREATE_TRY(dalloc(c, &c->z, (size_t)R * c->din_pad));
     CREATE_TRY(dalloc(c, &c->hu, (size_t)MAX_SPLITS * R * g.d_head_hidden));
-    CREATE_TRY(dalloc(c, &c->a, (size_t)R * d));
+    auto act_alloc = [&](ActBuf *a, size_t n) -> hipError_t {
+        hipError_t e = dalloc(c, &a->f, n);
+        if (e == hipSuccess) e = dalloc(c, &a->hi, n);
+        if (e == hipSuccess) e = dalloc(c, &a->lo, n);
+        return e;
+    };
+    CREATE_TRY(act_alloc(&c->a, (size_t)R * d));
+    CREATE_TRY(act_alloc(&c->o, (size_t)R * c->d_q));
+    CREATE_TRY(act_alloc(&c->h, (size_t)R * F));
+    CREATE_TRY(act_alloc(&c->z, (size_t)R * c->din_pad));
     CREATE_TRY(dalloc(c, &c->q, (size_t)R * c->d_q));
-    CREATE_TRY(dalloc(c, &c->o, (size_t)R * c->d_q));
-    CREATE_TRY(dalloc(c, &c->h, (size_t)R * F));
+    {
+        // split-KV attention partials: as many splits as fit 64 MiB, at most 64
+        const size_t per_split = (size_t)R * c->d_q;
+        c->att_max_splits = (int)std::max<size_t>(1, std::min<size_t>(64, ((size_t)16 << 20) / per_split));
+        CREATE_TRY(dalloc(c, &c->att_o, per_split * c->att_max_splits));
+        CREATE_TRY(dalloc(c, &c->att_m, (size_t)R * g.n_heads * c->att_max_splits));
+        CREATE_TRY(dalloc(c, &c->att_l, (size_t)R * g.n_heads * c->att_max_splits));
+    }
     CREATE_TRY(dalloc(c, &c->logits, (size_t)R * V));
     c->logits_rows = R;
     CREATE_TRY(hipStreamSynchronize(c->stream));
@@ -350,10 +364,10 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         // kernel sums in a fixed order; gate/up and the LM head fuse SwiGLU / argmax instead
         const size_t ys = (size_t)c->rows_max * d, qs = (size_t)c->rows_max * c->d_qkv;
         // a product whose shape the streaming kernel cannot serve falls back to the generic kernel (one slice)
-        auto product = [&](const void *wt, const void *w, const float *X, float *Yp, size_t stride, int n, int kd) {
+        auto product = [&](const void *wt, const void *w, const ActBuf &X, float *Yp, size_t stride, int n, int kd) {
             int ns = launch_gemm_ws_partial(c, wt, X, Yp, stride, MAX_SPLITS, f.rows, n, kd, KC_GEMM);
             if (!ns) {
-                launch_gemm_ref(c, X, w, Yp, f.rows, n, kd, KC_GEMM);
+                launch_gemm_ref(c, X.f, w, Yp, f.rows, n, kd, KC_GEMM);
                 ns = 1;
             }
             return ns;
@@ -364,11 +378,11 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
             const int nq = product(L.wqkv_t, L.wqkv, c->a, c->qkv, qs, c->d_qkv, d);
             launch_rope_append(c, f, l, nq);
-            launch_attn_ref(c, f, l);
+            if (!launch_attn_mfma(c, f, l)) launch_attn_ref(c, f, l);
             ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
             launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
             if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, 2 * F, d, KC_GEMM_GATEUP)) {
-                launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
+                launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
                 launch_swiglu(c, f.rows);
             }
             ny = product(L.wdown_t, L.wdown, c->h, c->y, ys, d, F);
@@ -376,7 +390,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         launch_rmsnorm(c, f.rows, ny, c->final_norm, c->a, c->h_t);
         if (!launch_gemm_ws_argmax(c, c->lm_head_t, c->a, f.keep_logits ? c->logits : nullptr, f.rows, g.vocab, d,
                                    KC_LMHEAD)) {
-            launch_gemm_ref(c, c->a, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
+            launch_gemm_ref(c, c->a.f, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
             launch_argmax(c, f.rows);
         }
         return;
@@ -384,17 +398,17 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
     for (int l = 0; l < g.n_layers; ++l) {
         const LayerW &L = c->layers[l];
         launch_rmsnorm(c, f.rows, l == 0 ? 0 : 1, L.attn_norm, c->a, nullptr);     // + previous FFN update
-        launch_gemm_ref(c, c->a, L.wqkv, c->qkv, f.rows, c->d_qkv, d, KC_GEMM);
+        launch_gemm_ref(c, c->a.f, L.wqkv, c->qkv, f.rows, c->d_qkv, d, KC_GEMM);
         launch_rope_append(c, f, l, 1);
         launch_attn_ref(c, f, l);
-        launch_gemm_ref(c, c->o, L.wo, c->y, f.rows, d, c->d_q, KC_GEMM);
+        launch_gemm_ref(c, c->o.f, L.wo, c->y, f.rows, d, c->d_q, KC_GEMM);
         launch_rmsnorm(c, f.rows, 1, L.ffn_norm, c->a, nullptr);                   // + attention update
-        launch_gemm_ref(c, c->a, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
+        launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
         launch_swiglu(c, f.rows);
-        launch_gemm_ref(c, c->h, L.wdown, c->y, f.rows, d, F, KC_GEMM);
+        launch_gemm_ref(c, c->h.f, L.wdown, c->y, f.rows, d, F, KC_GEMM);
     }
     launch_rmsnorm(c, f.rows, 1, c->final_norm, c->a, c->h_t);
-    launch_gemm_ref(c, c->a, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
+    launch_gemm_ref(c, c->a.f, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
     launch_argmax(c, f.rows);
 }
 
@@ -656,7 +670,7 @@ extern "C" int wisv_last_round_ms(wisv_ctx *ctx, float *ms) {
     return WISV_OK;
 }
 
-static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm_qkv_o_down", "gemm_gate_up", "rope_append", "attention",
+static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm_qkv_o_down", "gemm_gate_up", "rope_append", "attention", "attention_combine",
                                             "swiglu", "lm_head", "argmax", "head", "decide"};
 
 extern "C" int wisv_profile_enable(wisv_ctx *ctx, int32_t on) {

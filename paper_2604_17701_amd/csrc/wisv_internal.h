@@ -44,10 +44,29 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// An activation tensor handed to a matrix product: the float values (read by the generic kernels and by the
+// decision head) and, for the MFMA kernels, the same values as two bf16 planes with x = hi + lo to 2^-17.
+// Every kernel that produces such a tensor writes all three.
+struct ActBuf {
+    float *f;
+    bf16_t *hi, *lo;
+};
+__device__ __forceinline__ void split2(float v, bf16_t &hi, bf16_t &lo) {
+    hi = f32_to_bf16(v);
+    lo = f32_to_bf16(v - bf16_to_f32(hi));
+}
+__device__ __forceinline__ void act_store(const ActBuf &a, size_t i, float v) {
+    bf16_t h, l;
+    split2(v, h, l);
+    a.f[i] = v;
+    a.hi[i] = h;
+    a.lo[i] = l;
+}
+
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
 enum KernelClass {
-    KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_SWIGLU, KC_LMHEAD, KC_ARGMAX,
-    KC_HEAD, KC_DECIDE, KC_COUNT
+    KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_LMHEAD,
+    KC_ARGMAX, KC_HEAD, KC_DECIDE, KC_COUNT
 };
 
 // ---------------------------------------------------------------- the context
@@ -70,7 +89,7 @@ struct Ctx {
     void *head_w1, *head_b1, *head_w2, *head_b2;
     void *head_w1_pad, *head_w1_t;   // W1 with its rows zero-padded to din_pad columns; its re-tiled copy (bf16)
     int din_pad;                     // d_draft + d_model + d_csi rounded up to a multiple of 32
-    float *rope_cos, *rope_sin;   // [max_ctx][head_dim/2]
+    float *rope_cos, *rope_sin;      // [max_ctx][head_dim/2]
 
     // KV cache [n_layers][max_batch][2][n_kv_heads][max_ctx][head_dim]
     void *kv;
@@ -93,9 +112,12 @@ struct Ctx {
     int32_t *row_slot, *row_pos, *amax, *scored;
     float *x, *y, *qkv, *gu, *h_t, *logits;   // y and qkv hold up to MAX_SPLITS partial slices
     float *cand_val;
-    float *z, *hu;                // decision head: gathered inputs [rows][din_pad], first-layer slices
     int32_t *cand_idx;
-    float *a, *q, *o, *h;         // activations handed to the matrix products (float in both paths)
+    float *q;                     // rotated queries [rows][d_q]
+    ActBuf a, o, h, z;            // normalised activations, attention output, SwiGLU output, head input
+    float *hu;                    // decision head: first-layer slices
+    float *att_o, *att_m, *att_l; // split-KV attention partials: [split][rows][heads][head_dim], [split][rows][heads]
+    int att_max_splits;
     size_t logits_rows;
 
     // timing
@@ -124,16 +146,18 @@ struct Fwd {
 // ---------------------------------------------------------------- kernel launchers (kernels_ref.hip)
 void launch_prep_rows(Ctx *c, const Fwd &f);
 void launch_embed(Ctx *c, const Fwd &f);
-// x += sum of n_partial slices of y (if n_partial > 0); out = RMSNorm(x) * g; optional float copy
-void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, void *out, float *out_f32);
+// x += sum of n_partial slices of y (if n_partial > 0); out = RMSNorm(x) * g; optional second float copy
+void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, const ActBuf &out, float *out_f32);
 // Y[rows, n] = A[rows, kd] * W[n, kd]^T (float accumulate, float out)
-void launch_gemm_ref(Ctx *c, const void *A, const void *W, float *Y, int rows, int n, int kd, int kclass);
+void launch_gemm_ref(Ctx *c, const float *A, const void *W, float *Y, int rows, int n, int kd, int kclass);
 void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial);
 void launch_attn_ref(Ctx *c, const Fwd &f, int layer);
 void launch_swiglu(Ctx *c, int rows);
 void launch_argmax(Ctx *c, int rows);
-void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in_dev, const wisv_round_out &out_dev);
 void launch_set_pred_next(Ctx *c, int slot, int row, int new_len);
+
+// ---------------------------------------------------------------- decision head + scan (kernels_head.hip)
+void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in_dev, const wisv_round_out &out_dev);
 void launch_pad_cols(Ctx *c, const void *src, void *dst, int rows, int cols, int cols_pad);
 
 // ---------------------------------------------------------------- weight-streaming GEMM (kernels_gemm.hip)
@@ -141,10 +165,16 @@ constexpr int MAX_SPLITS = 8;
 bool ws_supported(const Ctx *c, int rows, int kd);
 int ws_padded_row_blocks(int n_rows);
 void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb);
-int launch_gemm_ws_partial(Ctx *c, const void *Wt, const void *X, float *Yp, size_t split_stride, int max_splits,
+int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
                            int rows, int n, int kd, int kclass);
-bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const void *X, void *H, int rows, int two_f, int kd, int kclass);
-bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const void *X, float *logits, int rows, int n, int kd, int kclass);
+bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int two_f, int kd,
+                           int kclass);
+bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass);
+
+// ---------------------------------------------------------------- split-KV MFMA attention (kernels_attn.hip)
+// true if the shape is served (bf16 cache, head_dim 128, at most 64 query rows per KV head); then c->o holds
+// the attention output of every row
+bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer);
 
 // records the event pair of one launch when profiling is on
 struct ProfScope {
