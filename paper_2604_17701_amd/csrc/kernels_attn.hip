@@ -81,28 +81,35 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
         for (int dt = 0; dt < 8; ++dt) oacc[nq][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- chunk loop.  Thread tid moves 16-byte segment (tid + 256 i) of the chunk's K and V rows.
-    uint4 kreg[4], vreg[4];
-    auto fetch = [&](int c) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i, key = min(c * CHUNK + (idx >> 4), n_keys - 1), seg = idx & 15;
-            kreg[i] = *reinterpret_cast<const uint4 *>(kc + (size_t)key * HD + seg * 8);
-            vreg[i] = *reinterpret_cast<const uint4 *>(vc + (size_t)key * HD + seg * 8);
-        }
-    };
+    // ---- chunk loop.  Thread tid moves 16-byte segment `seg` of staged rows krow, krow + 16, krow + 32, krow + 48
+    //      of the chunk's K and V.
+    // (named registers rather than arrays: the prefetched chunk must stay in VGPRs across the loop)
+    uint4 k0, k1, k2, k3, v0, v1, v2, v3;
+    const int seg = tid & 15, krow = tid >> 4;               // segment i covers staged row krow + 16 i
+#define WISV_ATTN_LOAD(c_, i_, kr_, vr_)                                                      \
+    {                                                                                         \
+        const int key_ = min((c_) * CHUNK + krow + 16 * (i_), n_keys - 1);                    \
+        kr_ = *reinterpret_cast<const uint4 *>(kc + (size_t)key_ * HD + seg * 8);             \
+        vr_ = *reinterpret_cast<const uint4 *>(vc + (size_t)key_ * HD + seg * 8);             \
+    }
+#define WISV_ATTN_FETCH(c_)          \
+    WISV_ATTN_LOAD(c_, 0, k0, v0)    \
+    WISV_ATTN_LOAD(c_, 1, k1, v1)    \
+    WISV_ATTN_LOAD(c_, 2, k2, v2)    \
+    WISV_ATTN_LOAD(c_, 3, k3, v3)
+#define WISV_ATTN_PUT(i_, kr_, vr_)                                                                        \
+    *reinterpret_cast<uint4 *>(buf + (krow + 16 * (i_)) * PITCH + seg * 16) = kr_;                         \
+    *reinterpret_cast<uint4 *>(buf + CHUNK * PITCH + (krow + 16 * (i_)) * PITCH + seg * 16) = vr_;
     const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
-    if (c_begin < c_end) fetch(c_begin);
+    if (c_begin < c_end) { WISV_ATTN_FETCH(c_begin) }
     for (int c = c_begin; c < c_end; ++c) {
         unsigned char *buf = lds + (size_t)((c - c_begin) & 1) * BUF_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i, key = idx >> 4, seg = idx & 15;
-            *reinterpret_cast<uint4 *>(buf + key * PITCH + seg * 16) = kreg[i];
-            *reinterpret_cast<uint4 *>(buf + CHUNK * PITCH + key * PITCH + seg * 16) = vreg[i];
-        }
+        WISV_ATTN_PUT(0, k0, v0)
+        WISV_ATTN_PUT(1, k1, v1)
+        WISV_ATTN_PUT(2, k2, v2)
+        WISV_ATTN_PUT(3, k3, v3)
         __syncthreads();   // chunk c staged; the other buffer is free (everyone finished chunk c - 1)
-        if (c + 1 < c_end) fetch(c + 1);
+        if (c + 1 < c_end) { WISV_ATTN_FETCH(c + 1) }
         const unsigned char *kb = buf + (16 * wave) * PITCH, *vb = buf + CHUNK * PITCH + (16 * wave) * PITCH;
         const int kbase = c * CHUNK + 16 * wave;
         if (kbase >= n_keys) continue;
@@ -167,6 +174,10 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
             }
         }
     }
+
+#undef WISV_ATTN_FETCH
+#undef WISV_ATTN_LOAD
+#undef WISV_ATTN_PUT
 
     // ---- sums over the four lane groups (each held the keys 4 bg + r of every tile), fixed order
 #pragma unroll
@@ -267,10 +278,10 @@ bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer) {
     a.H = g.n_heads; a.G = g.n_kv_heads; a.rep = rep; a.K = f.k; a.max_ctx = g.max_ctx; a.rows = f.rows;
     a.row_slot = c->row_slot; a.row_pos = c->row_pos;
     a.po = c->att_o; a.pm = c->att_m; a.pl = c->att_l;
-    // enough workgroups to cover the chip a few times, at most one split per 64-key chunk
+    // enough workgroups to cover the chip twice, at least two 64-key chunks per split
     const int n_chunks = (f.max_len_ub + CHUNK - 1) / CHUNK;
-    const int want = (1024 + f.batch * g.n_kv_heads - 1) / (f.batch * g.n_kv_heads);
-    a.n_splits = std::max(1, std::min(std::min(want, n_chunks), c->att_max_splits));
+    const int want = (512 + f.batch * g.n_kv_heads - 1) / (f.batch * g.n_kv_heads);
+    a.n_splits = std::max(1, std::min(std::min(want, (n_chunks + 1) / 2), c->att_max_splits));
     dim3 grid(a.n_splits, g.n_kv_heads, f.batch);
     {
         ProfScope ps(c, KC_ATTN);

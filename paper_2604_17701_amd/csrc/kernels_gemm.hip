@@ -81,6 +81,7 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
     const int my0 = wk * sub, myn = max(0, min(sub, ntile - my0));
     const int rb0 = (blockIdx.x * WR + wr) * RB;
     const bool active = rb0 < g.nrb;                               // RB * WR divides nrb (padded)
+    const int m_base = blockIdx.z * (16 * NT), Mt = min(16 * NT, g.M - m_base);   // this workgroup's rows
 
     // ---- start the weight stream before anything else: it does not depend on the activations
     const u32x4 *wp[RB];
@@ -103,17 +104,17 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
 
     // ---- activations: chunk ch holds, for every k-slice w, its tiles [ch kcw, (ch+1) kcw) as
     //      lds[ch & 1][plane][w][m][kcw * 64 + 16 bytes]; the 16 spreads rows over the banks
-    const int kcw = g.kcw, pitch = kcw * 64 + 16, wk_bytes = g.M * pitch, plane_bytes = WK * wk_bytes,
+    const int kcw = g.kcw, pitch = kcw * 64 + 16, wk_bytes = Mt * pitch, plane_bytes = WK * wk_bytes,
               buf_bytes = 2 * plane_bytes;
     const int nchunk = (sub + kcw - 1) / kcw;
     auto stage = [&](int ch) {
         unsigned char *dst = lds + (size_t)(ch & 1) * buf_bytes;
-        const int vec_per_row = kcw * 4, per_wk = g.M * vec_per_row;
+        const int vec_per_row = kcw * 4, per_wk = Mt * vec_per_row;
         for (int i = tid; i < WK * per_wk; i += NTH) {
             const int w = i / per_wk, rem = i - w * per_wk, m = rem / vec_per_row, v = rem - m * vec_per_row;
             const int lt = ch * kcw + (v >> 2), kt = w * sub + lt;          // tile within the slice / the workgroup range
             if (lt < sub && kt < ntile) {
-                const size_t off = (size_t)m * g.kd + (size_t)(kt0 + kt) * 32 + (v & 3) * 8;
+                const size_t off = (size_t)(m_base + m) * g.kd + (size_t)(kt0 + kt) * 32 + (v & 3) * 8;
                 unsigned char *d = dst + (size_t)w * wk_bytes + (size_t)m * pitch + v * 16;
                 *reinterpret_cast<uint4 *>(d) = *reinterpret_cast<const uint4 *>(g.Xhi + off);
                 *reinterpret_cast<uint4 *>(d + plane_bytes) = *reinterpret_cast<const uint4 *>(g.Xlo + off);
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
                     for (int t = 0; t < NT; ++t) {
                         const int m = t * 16 + bj;
                         uint4 bh = make_uint4(0, 0, 0, 0), bl = bh;
-                        if (m < g.M) {
+                        if (m < Mt) {
                             const unsigned char *p = buf + (size_t)m * pitch + ((kt + u - ch * kcw) * 32 + bg * 8) * 2;
                             bh = *reinterpret_cast<const uint4 *>(p);
                             bl = *reinterpret_cast<const uint4 *>(p + plane_bytes);
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
         float *out = g.Yp + (size_t)blockIdx.y * g.split_stride;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int m = t * 16 + bj;
+            const int m = m_base + t * 16 + bj;
             if (m >= g.M) continue;
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
@@ -203,7 +204,7 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
         const int F = g.N / 2;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int m = t * 16 + bj;
+            const int m = m_base + t * 16 + bj;
             if (m >= g.M) continue;
 #pragma unroll
             for (int pr = 0; pr < (RB + 1) / 2; ++pr) {
@@ -217,7 +218,7 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
     } else {   // EPI_ARGMAX: best (value, lowest index) of this wave's 16*RB features for every row
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int m = t * 16 + bj;
+            const int m = m_base + t * 16 + bj;
             float best = -INFINITY;
             int idx = 0x7fffffff;
 #pragma unroll
@@ -277,23 +278,23 @@ __global__ void k_argmax_cand(const float *__restrict__ val, const int32_t *__re
 // ------------------------------------------------------------------------------------------ launch
 // LDS bytes: activation chunk (two planes, WK slices; two buffers when a slice needs several chunks),
 // or the slice-reduction scratch if that is larger
-static size_t ws_lds(int M, int kcw, int sub, int NT, int RB, int WR, int WK) {
-    const size_t x = (size_t)(sub > kcw ? 2 : 1) * 2 * WK * M * (kcw * 64 + 16);
+static size_t ws_lds(int Mt, int kcw, int sub, int NT, int RB, int WR, int WK) {
+    const size_t x = (size_t)(sub > kcw ? 2 : 1) * 2 * WK * Mt * (kcw * 64 + 16);
     const size_t red = (size_t)WR * (WK - 1) * RB * NT * 1024;
     return std::max(x, red);
 }
 
 template <int NT, int RB, int WR, int WK, int U, int EPI>
 static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
-    const int sub = (g.kt_per_split + WK - 1) / WK;
+    const int sub = (g.kt_per_split + WK - 1) / WK, Mt = std::min(g.M, 16 * NT);
     // largest chunk (a multiple of U) within the soft budget, else within what a CU has
     int kcw = (sub + U - 1) / U * U;
     for (size_t budget : {soft_budget, (size_t)150 * 1024}) {
         kcw = (sub + U - 1) / U * U;
-        while (kcw > U && ws_lds(g.M, kcw, sub, NT, RB, WR, WK) > budget) kcw = (kcw / 2 + U - 1) / U * U;
-        if (ws_lds(g.M, kcw, sub, NT, RB, WR, WK) <= budget) break;
+        while (kcw > U && ws_lds(Mt, kcw, sub, NT, RB, WR, WK) > budget) kcw = (kcw / 2 + U - 1) / U * U;
+        if (ws_lds(Mt, kcw, sub, NT, RB, WR, WK) <= budget) break;
     }
-    const size_t lds = ws_lds(g.M, kcw, sub, NT, RB, WR, WK);
+    const size_t lds = ws_lds(Mt, kcw, sub, NT, RB, WR, WK);
     if (lds > 150 * 1024) return false;
     g.kcw = kcw;
     static bool opted_in = false;     // per instantiation
@@ -303,13 +304,29 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
             return false;
         opted_in = true;
     }
-    dim3 grid((g.nrb / RB + WR - 1) / WR, splits);
+    dim3 grid((g.nrb / RB + WR - 1) / WR, splits, (g.M + 16 * NT - 1) / (16 * NT));
     hipLaunchKernelGGL((k_gemm_ws<NT, RB, WR, WK, U, EPI>), grid, dim3(64 * WR * WK), lds, c->stream, g);
     return true;
 }
 
+// More than 16 rows: a workgroup of eight waves shares one activation chunk in LDS (up to 128 rows, the
+// grid's z dimension walks further row tiles), two row-blocks per wave.
+template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits) {
+    const int nt = std::min(8, (g.M + 15) / 16);
+    switch (nt) {
+        case 2: return launch_ws_t<2, 2, 8, 1, 4, EPI>(c, g, splits, 72 * 1024);
+        case 3: return launch_ws_t<3, 2, 8, 1, 4, EPI>(c, g, splits, 72 * 1024);
+        case 4: return launch_ws_t<4, 2, 8, 1, 4, EPI>(c, g, splits, 100 * 1024);
+        case 5: return launch_ws_t<5, 2, 8, 1, 2, EPI>(c, g, splits, 100 * 1024);
+        case 6: return launch_ws_t<6, 2, 8, 1, 2, EPI>(c, g, splits, 100 * 1024);
+        case 7: return launch_ws_t<7, 2, 8, 1, 2, EPI>(c, g, splits, 140 * 1024);
+        case 8: return launch_ws_t<8, 2, 8, 1, 2, EPI>(c, g, splits, 140 * 1024);
+        default: return false;
+    }
+}
+
 bool ws_supported(const Ctx *c, int rows, int kd) {
-    return c->bf16 && kd % 32 == 0 && rows <= 96;
+    return c->bf16 && kd % 32 == 0 && rows >= 1;
 }
 
 static void fill_args(GemmArgs &g, const void *Wt, const ActBuf &X, int rows, int n, int kd) {
@@ -327,25 +344,21 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     GemmArgs g{};
     fill_args(g, Wt, X, rows, n, kd);
     g.Yp = Yp; g.split_stride = split_stride;
-    const int nt = (rows + 15) / 16;
-    // splits: about 8192 waves in all for up to 16 rows (2 x 4 waves per workgroup), 2048 beyond; a wave keeps
-    // at least 4 k-tiles
-    const int wk = nt == 1 ? 4 : 1, rb = nt == 1 ? 1 : (nt <= 3 ? 2 : 4);
-    const int want = nt == 1 ? 8192 : 2048;
-    int s = (want + (g.nrb / rb) * wk - 1) / ((g.nrb / rb) * wk);
-    s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / (4 * wk)))));
+    int s;
+    if (rows <= 16) {
+        // about 8192 waves in all (2 x 4 waves per workgroup), a wave keeps at least 4 k-tiles
+        s = (8192 + g.nrb * 4 - 1) / (g.nrb * 4);
+        s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 16))));
+    } else {
+        // at least ~512 workgroups of eight waves over (row-block groups) x (row tiles) x splits
+        const int wgs = (g.nrb / 16) * ((rows + 127) / 128);
+        s = (512 + wgs - 1) / std::max(1, wgs);
+        s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 16))));
+    }
     g.kt_per_split = (g.nkt + s - 1) / s;
     const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
-    bool ok;
-    switch (nt) {
-        case 1: ok = launch_ws_t<1, 1, 2, 4, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024); break;
-        case 2: ok = launch_ws_t<2, 2, 4, 1, 4, EPI_PARTIAL>(c, g, splits, 60 * 1024); break;
-        case 3: ok = launch_ws_t<3, 2, 4, 1, 4, EPI_PARTIAL>(c, g, splits, 60 * 1024); break;
-        case 4: ok = launch_ws_t<4, 4, 2, 1, 2, EPI_PARTIAL>(c, g, splits, 72 * 1024); break;
-        case 5: ok = launch_ws_t<5, 4, 2, 1, 2, EPI_PARTIAL>(c, g, splits, 72 * 1024); break;
-        case 6: ok = launch_ws_t<6, 4, 2, 1, 2, EPI_PARTIAL>(c, g, splits, 72 * 1024); break;
-        default: ok = false;
-    }
+    const bool ok = rows <= 16 ? launch_ws_t<1, 1, 2, 4, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
+                               : launch_ws_many<EPI_PARTIAL>(c, g, splits);
     return ok ? splits : 0;
 }
 
@@ -359,16 +372,9 @@ bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf
     g.nrb = 2 * ws_padded_row_blocks(two_f / 2);
     g.kt_per_split = g.nkt;
     g.H = H;
-    switch ((rows + 15) / 16) {
-        // few rows: the whole activation slice sits in LDS, four long-lived waves per workgroup
-        case 1: return launch_ws_t<1, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 140 * 1024);
-        case 2: return launch_ws_t<2, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 72 * 1024);
-        case 3: return launch_ws_t<3, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 72 * 1024);
-        case 4: return launch_ws_t<4, 4, 2, 1, 2, EPI_SWIGLU>(c, g, 1, 72 * 1024);
-        case 5: return launch_ws_t<5, 4, 2, 1, 2, EPI_SWIGLU>(c, g, 1, 72 * 1024);
-        case 6: return launch_ws_t<6, 4, 2, 1, 2, EPI_SWIGLU>(c, g, 1, 72 * 1024);
-        default: return false;
-    }
+    // few rows: the whole activation slice sits in LDS, four long-lived waves per workgroup
+    if (rows <= 16) return launch_ws_t<1, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 140 * 1024);
+    return launch_ws_many<EPI_SWIGLU>(c, g, 1);
 }
 
 // LM head with the argmax fused: greedy token of every row in c->amax; logits kept only on request
@@ -376,23 +382,14 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     GemmArgs g{};
     fill_args(g, Wt, X, rows, n, kd);
     g.kt_per_split = g.nkt;
+    g.n_cand = g.nrb;                     // at most one candidate slot per row-block
     g.Yp = logits;
     g.cand_val = c->cand_val; g.cand_idx = c->cand_idx;
-    g.n_cand = g.nrb;                     // at most one candidate slot per row-block
-    const int nt = (rows + 15) / 16;
-    const int slots = g.nrb / (nt == 1 ? 1 : (nt <= 3 ? 2 : 4));
+    const int slots = rows <= 16 ? g.nrb : g.nrb / 2;
     {
         ProfScope ps(c, kclass);
-        bool ok;
-        switch (nt) {
-            case 1: ok = launch_ws_t<1, 1, 8, 1, 4, EPI_ARGMAX>(c, g, 1, 36 * 1024); break;
-            case 2: ok = launch_ws_t<2, 2, 4, 1, 4, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
-            case 3: ok = launch_ws_t<3, 2, 4, 1, 4, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
-            case 4: ok = launch_ws_t<4, 4, 2, 1, 2, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
-            case 5: ok = launch_ws_t<5, 4, 2, 1, 2, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
-            case 6: ok = launch_ws_t<6, 4, 2, 1, 2, EPI_ARGMAX>(c, g, 1, 72 * 1024); break;
-            default: ok = false;
-        }
+        const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_ARGMAX>(c, g, 1, 36 * 1024)
+                                   : launch_ws_many<EPI_ARGMAX>(c, g, 1);
         if (!ok) return false;
     }
     {

@@ -140,17 +140,11 @@ void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in, const wis
                                din_pad, (const float *)in.hd, in.hd_row, in.n_hd, c->h_t, in.csi, in.stream_ids, in.proto,
                                in.draft_tokens, c->amax, c->d_pred_next, f.k, g.max_batch, gate_all, c->z, c->scored);
     }
-    // u = W1 z, at most 96 rows per launch of the streaming kernel
+    // u = W1 z
     bool streamed = c->head_w1_t != nullptr;
     if (streamed) {
-        for (int r0 = 0; r0 < f.rows && streamed; r0 += 96) {
-            const int rows = std::min(96, f.rows - r0);
-            const ActBuf zt{c->z.f + (size_t)r0 * din_pad, c->z.hi + (size_t)r0 * din_pad, c->z.lo + (size_t)r0 * din_pad};
-            const int ns = launch_gemm_ws_partial(c, c->head_w1_t, zt, c->hu + (size_t)r0 * dJ,
-                                                  ustride, r0 == 0 ? MAX_SPLITS : n_partial, rows, dJ, din_pad, KC_HEAD);
-            if (!ns || (r0 > 0 && ns != n_partial)) streamed = false;
-            else n_partial = ns;
-        }
+        n_partial = launch_gemm_ws_partial(c, c->head_w1_t, c->z, c->hu, ustride, MAX_SPLITS, f.rows, dJ, din_pad, KC_HEAD);
+        streamed = n_partial > 0;
     }
     if (!streamed) {
         n_partial = 1;

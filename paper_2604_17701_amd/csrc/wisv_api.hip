@@ -359,7 +359,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
     const int d = g.d_model, F = g.d_ff;
     launch_prep_rows(c, f);
     launch_embed(c, f);
-    if (c->ws_ok && f.rows <= 96) {
+    if (c->ws_ok) {
         // bf16 weight-streaming path: every product leaves k-split partial slices that the next
         // kernel sums in a fixed order; gate/up and the LM head fuse SwiGLU / argmax instead
         const size_t ys = (size_t)c->rows_max * d, qs = (size_t)c->rows_max * c->d_qkv;
@@ -372,6 +372,12 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             }
             return ns;
         };
+        auto gate_up = [&](const LayerW &L) {
+            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, 2 * F, d, KC_GEMM_GATEUP)) {
+                launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
+                launch_swiglu(c, f.rows);
+            }
+        };
         int ny = 0;
         for (int l = 0; l < g.n_layers; ++l) {
             const LayerW &L = c->layers[l];
@@ -381,10 +387,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             if (!launch_attn_mfma(c, f, l)) launch_attn_ref(c, f, l);
             ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
             launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
-            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, 2 * F, d, KC_GEMM_GATEUP)) {
-                launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
-                launch_swiglu(c, f.rows);
-            }
+            gate_up(L);
             ny = product(L.wdown_t, L.wdown, c->h, c->y, ys, d, F);
         }
         launch_rmsnorm(c, f.rows, ny, c->final_norm, c->a, c->h_t);
