@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default: the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copies", type=int, default=0,
+                    help="also run N plain 1 GiB copy kernels (known traffic, for scaling rocprofv3 memory counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: the verify round runs on ONE GPU (streams are independent; nothing is sharded): "
@@ -135,6 +137,14 @@ def main():
     res = rnd.results()
     verified = w.batch * w.k / (ms * 1e-3)
 
+    if a.calibration_copies:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(a.calibration_copies):
+            ctx.wisv_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- per-kernel durations: the same rounds again with a HIP event pair around every launch
     ctx.wisv_profile_enable(True)
     for _ in range(a.steps):
@@ -142,8 +152,11 @@ def main():
     ctx.wisv_profile_collect()
     prof = ctx.wisv_profile_read()
     ctx.wisv_profile_enable(False)
-    kernels = {n: {"ms_per_round": t / a.steps, "launches_per_round": c // a.steps, "avg_us": 1e3 * t / max(c, 1)}
-               for n, (t, c) in prof.items() if c}
+    # an empty event pair per round measures what the bracketing adds to every launch; it is subtracted
+    pair_us = 1e3 * prof["event_pair_overhead"][0] / max(prof["event_pair_overhead"][1], 1)
+    kernels = {n: {"ms_per_round": (t - 1e-3 * pair_us * c) / a.steps, "launches_per_round": c // a.steps,
+                   "avg_us": 1e3 * t / max(c, 1) - pair_us}
+               for n, (t, c) in prof.items() if c and n != "event_pair_overhead"}
     # algorithmic bytes each weight-streaming kernel class must read per round
     esz = 2 if m.dtype == "bf16" else 4
     d, f, nl = m.d_model, m.d_ff, m.n_layers
@@ -160,7 +173,9 @@ def main():
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                 "bytes_per_launch": per_launch, "avg_launch_us": k["avg_us"],
-                "timing": f"HIP event pair around every launch on the round's stream, {a.steps} rounds right after the timed ones"}
+                "event_pair_overhead_us": pair_us,
+                "timing": f"HIP event pair around every launch on the round's stream, {a.steps} rounds right after the timed ones, "
+                          "minus the duration of an empty event pair"}
     round_alg = w.algorithmic_bytes()
     out = {
         "metric": "verified draft tokens/sec + ms per verify round, 8B-shaped target, K=4",

@@ -196,10 +196,16 @@ int wisv_last_round_ms(wisv_ctx *ctx, float *ms);
  * on the ctx's stream.  wisv_profile_collect() waits for the stream and adds the elapsed times of the
  * launches since the last collect to per-class totals; wisv_profile_read() returns one class's name
  * (static string), accumulated milliseconds and launch count.  Enabling or disabling resets the totals.
+ * The class "event_pair_overhead" times one empty event pair per round: what the bracketing itself adds.
  * kclass runs from 0 until wisv_profile_read() returns WISV_EINVAL. */
 int wisv_profile_enable(wisv_ctx *ctx, int32_t on);
 int wisv_profile_collect(wisv_ctx *ctx);
 int wisv_profile_read(wisv_ctx *ctx, int32_t kclass, const char **name, double *total_ms, int64_t *launches);
+
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned
+ * device memory) on the ctx's stream: a kernel of known traffic, used to calibrate hardware memory counters
+ * when profiling the round. */
+int wisv_calibration_copy(wisv_ctx *ctx, void *dst, const void *src, size_t bytes);
 
 /* Message of the last error on this ctx ("" if none).  Never NULL. */
 const char *wisv_last_error(const wisv_ctx *ctx);

@@ -27,7 +27,7 @@ WISV_MAX_K = 16
 
 EXPORTS = ("wisv_ctx_create", "wisv_verify_round", "wisv_destroy", "wisv_prefill", "wisv_set_state",
            "wisv_get_state", "wisv_kv_import", "wisv_kv_export", "wisv_debug_copy", "wisv_last_round_ms",
-           "wisv_profile_enable", "wisv_profile_collect", "wisv_profile_read", "wisv_last_error")
+           "wisv_profile_enable", "wisv_profile_collect", "wisv_profile_read", "wisv_calibration_copy", "wisv_last_error")
 
 
 class WisvError(RuntimeError):
@@ -90,6 +90,7 @@ def load_library() -> C.CDLL:
         lib.wisv_profile_collect.argtypes = [C.c_void_p]
         lib.wisv_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                           C.POINTER(C.c_int64)]
+        lib.wisv_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         lib.wisv_last_error.argtypes = [C.c_void_p]
         lib.wisv_last_error.restype = C.c_char_p
         for name in EXPORTS:
@@ -259,6 +260,10 @@ class Context:
         ms = C.c_float()
         self._check(self._lib.wisv_last_round_ms(self._h, C.byref(ms)))
         return ms.value
+
+    def wisv_calibration_copy(self, dst: torch.Tensor, src: torch.Tensor):
+        n = src.numel() * src.element_size()
+        self._check(self._lib.wisv_calibration_copy(self._h, dst.data_ptr(), src.data_ptr(), n))
 
     def wisv_profile_enable(self, on: bool):
         self._check(self._lib.wisv_profile_enable(self._h, 1 if on else 0))

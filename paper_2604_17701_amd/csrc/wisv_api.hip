@@ -511,6 +511,7 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
     f.max_len_ub = len_ub;
 
     HIP_TRY(c, hipEventRecord(c->ev_round[0], c->stream));
+    { ProfScope empty(c, KC_EMPTY); }   // an event pair with nothing in between: what the bracketing itself costs
     enqueue_forward(c, f);
     launch_head_decide(c, f, din, dout);
     HIP_TRY(c, hipEventRecord(c->ev_round[1], c->stream));
@@ -673,8 +674,23 @@ extern "C" int wisv_last_round_ms(wisv_ctx *ctx, float *ms) {
     return WISV_OK;
 }
 
+__global__ void k_calibration_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+extern "C" int wisv_calibration_copy(wisv_ctx *ctx, void *dst, const void *src, size_t bytes) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (!dst || !src || bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16)
+        return fail(c, WISV_EINVAL, "calibration copy needs 16-byte aligned pointers and a multiple of 16 bytes");
+    HIP_TRY(c, hipSetDevice(c->cfg.device_id));
+    hipLaunchKernelGGL(k_calibration_copy, dim3(8192), dim3(256), 0, c->stream, (const uint4 *)src, (uint4 *)dst, bytes / 16);
+    HIP_TRY(c, hipGetLastError());
+    return WISV_OK;
+}
+
 static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm_qkv_o_down", "gemm_gate_up", "rope_append", "attention", "attention_combine",
-                                            "swiglu", "lm_head", "argmax", "head", "decide"};
+                                            "swiglu", "lm_head", "argmax", "head", "decide", "event_pair_overhead"};
 
 extern "C" int wisv_profile_enable(wisv_ctx *ctx, int32_t on) {
     if (!ctx) return WISV_EINVAL;

@@ -66,7 +66,7 @@ __device__ __forceinline__ void act_store(const ActBuf &a, size_t i, float v) {
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
 enum KernelClass {
     KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_LMHEAD,
-    KC_ARGMAX, KC_HEAD, KC_DECIDE, KC_COUNT
+    KC_ARGMAX, KC_HEAD, KC_DECIDE, KC_EMPTY, KC_COUNT
 };
 
 // ---------------------------------------------------------------- the context
