@@ -1,5 +1,5 @@
 // Weight-streaming bf16 GEMM for a small number of activation rows (the memory-bound regime of the
-// verify round: every weight byte is read once per round and meets at most a few dozen rows).
+// verify round: every weight byte is read once per round and meets at most a few hundred rows).
 //
 // Y[m, n] = sum_k X[m, k] W[n, k] is computed "swapped": the 16x16x32 MFMA takes a 16-row block of W as
 // its A operand and 16 activation rows as its B operand, so the output-feature dimension fills the
@@ -10,9 +10,12 @@
 // exact to about 2^-17 while the weights stay bf16; the second MFMA costs issue slots this memory-bound
 // kernel has to spare.
 //
-// A workgroup is WR x WK waves: WR groups of RB row-blocks, and WK slices of the workgroup's k-range whose
-// accumulators are added through LDS in slice order.  Small matrices need the k-slicing to put enough
-// waves in flight to pull HBM bandwidth; the grid's y dimension splits k further into partial outputs.
+// A workgroup is WR x WK waves: WR groups of RB row-blocks share the activation chunk in LDS, and WK slices
+// of the workgroup's k-range whose accumulators are added through LDS in slice order.  The grid's y
+// dimension splits k into partial outputs, its z dimension walks tiles of 16 NT rows.
+// The weight stream is software-pipelined through a ring of U register slots: the steady-state loop has no
+// branches, and every slot is refilled right after the MFMAs that read it (scheduling barriers keep that
+// order), so that the compiler's wait counts let U loads stay in flight.
 #include <algorithm>
 
 #include "wisv_internal.h"
@@ -25,19 +28,26 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------------ re-tiling
 // out[((rb * nkt + kt) * 64 + lane) * 8 + e] = W[row(rb, lane % 16)][32 kt + 8 (lane / 16) + e]
-// pair_rows > 0: W stacks two matrices of pair_rows rows each (gate over up); row-blocks alternate
-// between them so that a wave owning blocks 2p and 2p+1 holds gate and up of the same 16 features.
+// pair_rows > 0: W stacks two matrices of pair_rows rows each (gate over up); row-block rb then holds
+// gate rows 8rb..8rb+7 in its rows 0..7 and up rows 8rb..8rb+7 in its rows 8..15, so that one MFMA tile
+// carries both halves of SwiGLU for 8 features.
 __global__ void k_retile(const bf16_t *__restrict__ W, int n_rows, int kd, int nrb, int nkt, int pair_rows,
                          uint4 *__restrict__ out) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)nrb * nkt * 64) return;
     const int lane = idx & 63;
     const size_t tile = idx >> 6;
-    const int kt = tile % nkt, rb = tile / nkt;
+    const int kt = tile % nkt, rb = tile / nkt, i = lane & 15;
     int row;
-    if (pair_rows > 0) row = (rb & 1) * pair_rows + (rb >> 1) * 16 + (lane & 15);
-    else row = rb * 16 + (lane & 15);
-    const bool valid = pair_rows > 0 ? ((rb >> 1) * 16 + (lane & 15)) < pair_rows : row < n_rows;
+    bool valid;
+    if (pair_rows > 0) {
+        const int f = rb * 8 + (i & 7);
+        row = (i >> 3) * pair_rows + f;
+        valid = f < pair_rows;
+    } else {
+        row = rb * 16 + i;
+        valid = row < n_rows;
+    }
     uint4 v = make_uint4(0, 0, 0, 0);
     if (valid) v = *reinterpret_cast<const uint4 *>(W + (size_t)row * kd + 32 * kt + 8 * (lane >> 4));
     out[idx] = v;
@@ -50,8 +60,10 @@ void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, voi
                        n_rows, kd, nrb, nkt, pair_rows, (uint4 *)out);
 }
 
-// row-blocks are padded to a multiple of 8 so that a workgroup may own 1, 2, 4 or 8 of them
-int ws_padded_row_blocks(int n_rows) { return ((n_rows + 15) / 16 + 7) / 8 * 8; }
+// row-blocks are padded to a multiple of 16 so that a workgroup may own up to 16 of them
+int ws_padded_row_blocks(int n_rows) { return ((n_rows + 15) / 16 + 15) / 16 * 16; }
+// gate/up pairs: 8 features per row-block
+int ws_padded_pair_blocks(int features) { return ((features + 7) / 8 + 15) / 16 * 16; }
 
 // ------------------------------------------------------------------------------------------ the GEMM
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
@@ -63,7 +75,7 @@ struct GemmArgs {
     int kcw;                   // k-tiles per wave staged in LDS at a time (a multiple of the prefetch depth)
     float *Yp;                 // EPI_PARTIAL: [S][split_stride];  EPI_ARGMAX with logits != null: [M][N]
     size_t split_stride;
-    ActBuf H;                  // EPI_SWIGLU: [M][N/2] float + planes
+    ActBuf H;                  // EPI_SWIGLU: [M][N] float + planes (N = features)
     float *cand_val;           // EPI_ARGMAX: [M][n_cand]
     int32_t *cand_idx;
     int n_cand;
@@ -122,6 +134,25 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
         }
     };
     const int bj = lane & 15, bg = lane >> 4;
+    // B operands of one k-tile: lanes whose row does not exist read row Mt - 1 and are zeroed (no branch)
+    auto mfma_tile = [&](const unsigned char *buf, int lt, const u32x4 *a) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int m = t * 16 + bj;
+            const unsigned char *p = buf + (size_t)min(m, Mt - 1) * pitch + (lt * 32 + bg * 8) * 2;
+            uint4 bh = *reinterpret_cast<const uint4 *>(p);
+            uint4 bl = *reinterpret_cast<const uint4 *>(p + plane_bytes);
+            if (m >= Mt) { bh = make_uint4(0, 0, 0, 0); bl = bh; }
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                u32x4 av = a[r];
+                acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&av),
+                                                                   *reinterpret_cast<bf16x8 *>(&bh), acc[r][t], 0, 0, 0);
+                acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&av),
+                                                                   *reinterpret_cast<bf16x8 *>(&bl), acc[r][t], 0, 0, 0);
+            }
+        }
+    };
     stage(0);
     for (int ch = 0; ch < nchunk; ++ch) {
         __syncthreads();   // chunk ch is staged; everyone is done with the buffer chunk ch + 1 goes to
@@ -129,7 +160,21 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
         if (!active) continue;
         const unsigned char *buf = lds + (size_t)(ch & 1) * buf_bytes + (size_t)wk * wk_bytes;
         const int kend = min(myn, (ch + 1) * kcw);
-        for (int kt = ch * kcw; kt < kend; kt += U) {
+        int kt = ch * kcw;
+        // steady state: U tiles consumed and U refills issued per pass, no conditionals in between
+        for (; kt + U <= kend && kt + 2 * U <= myn; kt += U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                mfma_tile(buf, kt + u - ch * kcw, abuf[u]);
+                // the slot is free once its MFMAs have issued: refill it, and keep this order
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < RB; ++r) abuf[u][r] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u + U) * 64);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // the last tiles of the slice (and slices shorter than 2 U): guarded
+        for (; kt < kend; kt += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (kt + u < kend) {
@@ -139,23 +184,7 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
                         a[r] = abuf[u][r];
                         if (kt + u + U < myn) abuf[u][r] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u + U) * 64);
                     }
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const int m = t * 16 + bj;
-                        uint4 bh = make_uint4(0, 0, 0, 0), bl = bh;
-                        if (m < Mt) {
-                            const unsigned char *p = buf + (size_t)m * pitch + ((kt + u - ch * kcw) * 32 + bg * 8) * 2;
-                            bh = *reinterpret_cast<const uint4 *>(p);
-                            bl = *reinterpret_cast<const uint4 *>(p + plane_bytes);
-                        }
-#pragma unroll
-                        for (int r = 0; r < RB; ++r) {
-                            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                *reinterpret_cast<bf16x8 *>(&a[r]), *reinterpret_cast<bf16x8 *>(&bh), acc[r][t], 0, 0, 0);
-                            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                *reinterpret_cast<bf16x8 *>(&a[r]), *reinterpret_cast<bf16x8 *>(&bl), acc[r][t], 0, 0, 0);
-                        }
-                    }
+                    mfma_tile(buf, kt + u - ch * kcw, a);
                 }
             }
         }
@@ -183,7 +212,7 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
         return;
     }
 
-    // ---- epilogue.  acc[r][t][e] = Y[m = 16 t + lane % 16][n = 16 (rb0 + r) + 4 (lane / 16) + e]
+    // ---- epilogue.  acc[r][t][e] = Y[m = m_base + 16 t + lane % 16][row 4 (lane / 16) + e of row-block rb0 + r]
     if (EPI == EPI_PARTIAL) {
         float *out = g.Yp + (size_t)blockIdx.y * g.split_stride;
 #pragma unroll
@@ -200,18 +229,23 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
             }
         }
     } else if (EPI == EPI_SWIGLU) {
-        // blocks rb0 + 2p hold gate, rb0 + 2p + 1 hold up of features 16 (rb0 / 2 + p) ..
-        const int F = g.N / 2;
+        // rows 0..7 of a block are gate, rows 8..15 up, of features 8 (rb0 + r) ..: lanes 32..63 hold the up
+        // values that lanes 0..31 need
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int m = m_base + t * 16 + bj;
-            if (m >= g.M) continue;
 #pragma unroll
-            for (int pr = 0; pr < (RB + 1) / 2; ++pr) {
-                const int f = ((rb0 >> 1) + pr) * 16 + bg * 4;
-                for (int e = 0; e < 4; ++e) {
-                    const float gt = acc[2 * pr][t][e], up = acc[2 * pr + (RB > 1 ? 1 : 0)][t][e];
-                    if (f + e < F) act_store(g.H, (size_t)m * F + f + e, gt / (1.0f + expf(-gt)) * up);
+            for (int r = 0; r < RB; ++r) {
+                floatx4 up;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) up[e] = __shfl_xor(acc[r][t][e], 32, 64);
+                if (bg < 2 && m < g.M) {
+                    const int f = (rb0 + r) * 8 + bg * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gt = acc[r][t][e];
+                        if (f + e < g.N) act_store(g.H, (size_t)m * g.N + f + e, gt / (1.0f + expf(-gt)) * up[e]);
+                    }
                 }
             }
         }
@@ -346,34 +380,33 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     g.Yp = Yp; g.split_stride = split_stride;
     int s;
     if (rows <= 16) {
-        // about 8192 waves in all (2 x 4 waves per workgroup), a wave keeps at least 4 k-tiles
-        s = (8192 + g.nrb * 4 - 1) / (g.nrb * 4);
-        s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 16))));
+        // one row-block per wave: split k until about 4096 waves stream, a wave keeps at least 8 k-tiles
+        s = (4096 + g.nrb - 1) / g.nrb;
+        s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 8))));
     } else {
         // at least ~512 workgroups of eight waves over (row-block groups) x (row tiles) x splits
         const int wgs = (g.nrb / 16) * ((rows + 127) / 128);
         s = (512 + wgs - 1) / std::max(1, wgs);
-        s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 16))));
+        s = std::max(1, std::min(s, std::min(std::min(max_splits, 8), std::max(1, g.nkt / 16))));
     }
     g.kt_per_split = (g.nkt + s - 1) / s;
     const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
-    const bool ok = rows <= 16 ? launch_ws_t<1, 1, 2, 4, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
+    const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
                                : launch_ws_many<EPI_PARTIAL>(c, g, splits);
     return ok ? splits : 0;
 }
 
-// gate/up with the SwiGLU fused (single split): H[rows][F] = silu(gate) * up.  The re-tiled matrix
-// alternates gate and up row-blocks, 2 * padded(F) in all.
-bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int two_f, int kd,
+// gate/up with the SwiGLU fused (single split): H[rows][F] = silu(gate) * up.  Every row-block of the
+// re-tiled matrix holds 8 gate and 8 up rows.
+bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
                            int kclass) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
-    fill_args(g, Wt, X, rows, two_f, kd);
-    g.nrb = 2 * ws_padded_row_blocks(two_f / 2);
+    fill_args(g, Wt, X, rows, features, kd);
+    g.nrb = ws_padded_pair_blocks(features);
     g.kt_per_split = g.nkt;
     g.H = H;
-    // few rows: the whole activation slice sits in LDS, four long-lived waves per workgroup
-    if (rows <= 16) return launch_ws_t<1, 2, 4, 1, 4, EPI_SWIGLU>(c, g, 1, 140 * 1024);
+    if (rows <= 16) return launch_ws_t<1, 1, 8, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
     return launch_ws_many<EPI_SWIGLU>(c, g, 1);
 }
 
@@ -388,7 +421,7 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     const int slots = rows <= 16 ? g.nrb : g.nrb / 2;
     {
         ProfScope ps(c, kclass);
-        const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_ARGMAX>(c, g, 1, 36 * 1024)
+        const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 8, EPI_ARGMAX>(c, g, 1, 70 * 1024)
                                    : launch_ws_many<EPI_ARGMAX>(c, g, 1);
         if (!ok) return false;
     }

@@ -229,7 +229,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     c->lm_head_t = nullptr;
     if (c->ws_ok) {
         auto retile = [&](void **dst, const void *src, int n_rows, int kd, int pair_rows) -> hipError_t {
-            const int nrb = pair_rows > 0 ? 2 * ws_padded_row_blocks(pair_rows) : ws_padded_row_blocks(n_rows);
+            const int nrb = pair_rows > 0 ? ws_padded_pair_blocks(pair_rows) : ws_padded_row_blocks(n_rows);
             char *p;
             hipError_t e = dalloc(c, &p, (size_t)nrb * 16 * kd * 2);
             if (e != hipSuccess) return e;
@@ -373,7 +373,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             return ns;
         };
         auto gate_up = [&](const LayerW &L) {
-            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, 2 * F, d, KC_GEMM_GATEUP)) {
+            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, F, d, KC_GEMM_GATEUP)) {
                 launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
                 launch_swiglu(c, f.rows);
             }

@@ -161,13 +161,14 @@ void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in_dev, const
 void launch_pad_cols(Ctx *c, const void *src, void *dst, int rows, int cols, int cols_pad);
 
 // ---------------------------------------------------------------- weight-streaming GEMM (kernels_gemm.hip)
-constexpr int MAX_SPLITS = 8;
+constexpr int MAX_SPLITS = 16;
 bool ws_supported(const Ctx *c, int rows, int kd);
 int ws_padded_row_blocks(int n_rows);
+int ws_padded_pair_blocks(int features);
 void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb);
 int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
                            int rows, int n, int kd, int kclass);
-bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int two_f, int kd,
+bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
                            int kclass);
 bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass);
 
