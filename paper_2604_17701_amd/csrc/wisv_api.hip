@@ -110,7 +110,9 @@ static void destroy_ctx(Ctx *c) {
     if (!c) return;
     (void)hipSetDevice(c->cfg.device_id);
     (void)hipStreamSynchronize(c->stream);
+    if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
     for (void *p : c->owned) (void)hipFree(p);
+    if (c->stream_owned) (void)hipStreamDestroy(c->stream);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     if (c->ev_round[0]) (void)hipEventDestroy(c->ev_round[0]);
     if (c->ev_round[1]) (void)hipEventDestroy(c->ev_round[1]);
@@ -140,6 +142,11 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     if (!c) return report(WISV_ENOMEM, "host allocation failed");
     c->cfg = *config;
     c->stream = (hipStream_t)config->hip_stream;
+    c->stream_owned = false;
+    c->graph_exec = nullptr;
+    c->graph_len_ub = -1;
+    memset(&c->graph_in, 0, sizeof c->graph_in);
+    memset(&c->graph_out, 0, sizeof c->graph_out);
     c->bf16 = config->dtype == WISV_BF16;
     c->esz = c->bf16 ? 2 : 4;
     c->d_q = config->n_heads * config->head_dim;
@@ -172,6 +179,10 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     const size_t esz = c->esz;
     const int d = g.d_model, F = g.d_ff, V = g.vocab, R = c->rows_max;
     CREATE_TRY(hipSetDevice(g.device_id));
+    if (!c->stream) {
+        CREATE_TRY(hipStreamCreate(&c->stream));
+        c->stream_owned = true;
+    }
     CREATE_TRY(hipEventCreate(&c->ev_round[0]));
     CREATE_TRY(hipEventCreate(&c->ev_round[1]));
 
@@ -510,10 +521,44 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
     f.keep_logits = in->flags & WISV_FLAG_KEEP_LOGITS;
     f.max_len_ub = len_ub;
 
+    // A device-I/O round repeated with identical arguments (a serving loop re-using its buffers) is captured
+    // into a HIP graph the second time it is seen and replayed from then on: one submission instead of a
+    // few hundred launches.  Positions are read from device state, so a replay stays valid while the upper
+    // bound of the cached lengths (which sizes the attention launch) is unchanged.
+    const bool graphable = dev_io && !c->profiling;
+    const bool same_call = graphable && c->graph_len_ub == len_ub && !memcmp(&c->graph_in, in, sizeof *in) &&
+                           !memcmp(&c->graph_out, out, sizeof *out);
     HIP_TRY(c, hipEventRecord(c->ev_round[0], c->stream));
-    { ProfScope empty(c, KC_EMPTY); }   // an event pair with nothing in between: what the bracketing itself costs
-    enqueue_forward(c, f);
-    launch_head_decide(c, f, din, dout);
+    if (same_call && c->graph_exec) {
+        HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->stream));
+    } else {
+        // calls that cannot be replayed (host I/O, profiling) run eagerly and leave the cached graph alone
+        if (graphable && c->graph_exec) {
+            (void)hipGraphExecDestroy(c->graph_exec);
+            c->graph_exec = nullptr;
+        }
+        const bool capture = same_call;   // the first call of a kind always runs eagerly (one-time kernel attribute set-up)
+        if (capture) HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+        { ProfScope empty(c, KC_EMPTY); }   // an event pair with nothing in between: what the bracketing itself costs
+        enqueue_forward(c, f);
+        launch_head_decide(c, f, din, dout);
+        if (capture) {
+            hipGraph_t graph = nullptr;
+            HIP_TRY(c, hipStreamEndCapture(c->stream, &graph));
+            hipError_t e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            if (e != hipSuccess) {
+                c->graph_exec = nullptr;
+                return fail(c, WISV_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
+            }
+            HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->stream));
+        }
+        if (graphable) {
+            memcpy(&c->graph_in, in, sizeof *in);     // bytewise, padding included: the key is compared with memcmp
+            memcpy(&c->graph_out, out, sizeof *out);
+            c->graph_len_ub = len_ub;
+        }
+    }
     HIP_TRY(c, hipEventRecord(c->ev_round[1], c->stream));
     HIP_TRY(c, hipGetLastError());
     c->last_rows = R;

@@ -78,6 +78,13 @@ struct LayerW {
 struct Ctx {
     wisv_config cfg;
     hipStream_t stream;
+    bool stream_owned;   // no stream was given: the ctx made its own (the null stream cannot be captured)
+
+    // the last device-I/O round, captured as a HIP graph when the same call comes a second time
+    hipGraphExec_t graph_exec;
+    wisv_round_in graph_in;
+    wisv_round_out graph_out;
+    int graph_len_ub;
     bool bf16;
     size_t esz;          // bytes per weight / cache element
     int d_q, d_kv, d_qkv, rows_max;

@@ -201,3 +201,42 @@ def test_small_bf16_decoder_synthetic_kv():
     w = replace(configs.get(2), model=replace(MID, head_dim=128, n_heads=4, n_kv_heads=1), batch=2, ctx=1100, k=8,
                 protos=(PROTO_SH, PROTO_FH), name="mid_bf16_synthkv", index=8)
     _run_workload(w, TOL_BF16, kv="synthetic")
+
+
+def test_repeated_device_round_replays_match_the_eager_round():
+    """A device-I/O round repeated with the same buffers is replayed from a captured graph: every replay,
+    with other GPU work and synchronisations in between and with the buffers' contents changed in place,
+    must give exactly what the eager host-I/O round gives for the same inputs."""
+    w = replace(configs.get(2), model=replace(MID, head_dim=128, n_heads=4, n_kv_heads=1), batch=2, ctx=700, k=5,
+                protos=(PROTO_SH, PROTO_FH), name="mid_bf16_replay", index=9)
+    dev = torch.device("cuda:0")
+    wd = gen.make_weights(w.model, w.seed, dev)
+    ctx = _ctx(w, wd)
+    for b in range(w.batch):
+        for l in range(w.model.n_layers):
+            k, v = gen.synthetic_kv(w, b, l, dev)
+            ctx.wisv_kv_import(b, l, k, v)
+        ctx.wisv_set_state(b, w.ctx, gen.synthetic_pred_next(w, b))
+    sid = np.arange(w.batch)
+    csi = gen.csi_features(w)
+    hds = [gen.draft_hidden(w, b) for b in range(w.batch)]
+    hd, row_map = gen.pack_hidden(w, hds, [list(range(w.k))] * w.batch)
+    nc = binding.WISV_FLAG_NO_COMMIT
+    rng = np.random.default_rng(3)
+    drafts = rng.integers(0, w.model.vocab, (w.batch, w.k)).astype(np.int32)
+    tau = np.full(w.batch, 0.5, np.float32)
+    rnd = ctx.device_round(sid, drafts, w.protos, hd, row_map, csi, tau, w.k, nc)
+    junk = torch.zeros(1 << 20, device=dev)
+    for it in range(6):
+        if it >= 2:   # new drafts and thresholds, written into the same device buffers
+            drafts = rng.integers(0, w.model.vocab, (w.batch, w.k)).astype(np.int32)
+            tau = np.full(w.batch, 0.2 + 0.1 * it, np.float32)
+            rnd.toks.copy_(torch.from_numpy(drafts.reshape(-1)))
+            rnd.tau.copy_(torch.from_numpy(tau))
+        rnd.run()
+        got = rnd.results()
+        junk.add_(1.0).sum().item()
+        want = ctx.wisv_verify_round(sid, drafts, w.protos, hd, row_map, csi, tau, w.k, nc)
+        for name in ("accepted_len", "correction_token", "target_argmax", "mismatch_mask", "status", "p_accept"):
+            assert np.array_equal(np.asarray(got[name]).reshape(-1), np.asarray(want[name]).reshape(-1)), (it, name)
+    ctx.wisv_destroy()
