@@ -79,7 +79,87 @@ struct GemmArgs {
     float *cand_val;           // EPI_ARGMAX: [M][n_cand]
     int32_t *cand_idx;
     int n_cand;
+    int gx, gz, gs;            // k_gemm_mm: row-block groups, row tiles and k-splits the 1-D grid decodes into
 };
+
+// ------------------------------------------------------------------------------------------ epilogues
+// acc[r][t][e] = Y[m = m_base + 16 t + lane % 16][row 4 (lane / 16) + e of row-block rb0 + r]; `split` is the
+// partial-output slice, `slot` the wave's candidate slot (one per group of RB row-blocks)
+template <int NT, int RB, int EPI>
+__device__ __forceinline__ void ws_epilogue(const GemmArgs &g, floatx4 (&acc)[RB][NT], int m_base, int rb0, int split,
+                                            int slot, int lane) {
+    const int bj = lane & 15, bg = lane >> 4;
+    if (EPI == EPI_PARTIAL) {
+        float *out = g.Yp + (size_t)split * g.split_stride;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int m = m_base + t * 16 + bj;
+            if (m >= g.M) continue;
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const int n = (rb0 + r) * 16 + bg * 4;
+                if (n + 3 < g.N && (g.N & 3) == 0) *reinterpret_cast<floatx4 *>(out + (size_t)m * g.N + n) = acc[r][t];
+                else
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < g.N) out[(size_t)m * g.N + n + e] = acc[r][t][e];
+            }
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        // rows 0..7 of a block are gate, rows 8..15 up, of features 8 (rb0 + r) ..: lanes 32..63 hold the up
+        // values that lanes 0..31 need
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int m = m_base + t * 16 + bj;
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                floatx4 up;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) up[e] = __shfl_xor(acc[r][t][e], 32, 64);
+                if (bg < 2 && m < g.M) {
+                    const int f = (rb0 + r) * 8 + bg * 4;
+                    float hv[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gt = acc[r][t][e];
+                        hv[e] = gt / (1.0f + expf(-gt)) * up[e];
+                    }
+                    if (f + 3 < g.N && (g.N & 3) == 0) act_store4(g.H, (size_t)m * g.N + f, hv[0], hv[1], hv[2], hv[3]);
+                    else
+                        for (int e = 0; e < 4; ++e)
+                            if (f + e < g.N) act_store(g.H, (size_t)m * g.N + f + e, hv[e]);
+                }
+            }
+        }
+    } else {   // EPI_ARGMAX: best (value, lowest index) of this wave's 16*RB features for every row
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int m = m_base + t * 16 + bj;
+            float best = -INFINITY;
+            int idx = 0x7fffffff;
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int n = (rb0 + r) * 16 + bg * 4 + e;
+                    const float v = acc[r][t][e];
+                    if (n < g.N) {
+                        if (g.Yp && m < g.M) g.Yp[(size_t)m * g.N + n] = v;
+                        if (v > best || (v == best && n < idx)) { best = v; idx = n; }
+                    }
+                }
+#pragma unroll
+            for (int o = 16; o < 64; o <<= 1) {
+                const float ov = __shfl_xor(best, o, 64);
+                const int oi = __shfl_xor(idx, o, 64);
+                if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+            }
+            if (bg == 0 && m < g.M) {
+                g.cand_val[(size_t)m * g.n_cand + slot] = best;
+                g.cand_idx[(size_t)m * g.n_cand + slot] = idx;
+            }
+        }
+    }
+}
 
 // NT: 16-row activation tiles per wave; RB: row-blocks per wave; WR x WK waves per workgroup; U: prefetch depth
 template <int NT, int RB, int WR, int WK, int U, int EPI>
@@ -212,73 +292,220 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
         return;
     }
 
-    // ---- epilogue.  acc[r][t][e] = Y[m = m_base + 16 t + lane % 16][row 4 (lane / 16) + e of row-block rb0 + r]
+    ws_epilogue<NT, RB, EPI>(g, acc, m_base, rb0, blockIdx.y, blockIdx.x * WR + wr, lane);
+}
+
+// ------------------------------------------------------------------------------------------ many rows
+// The compute-bound regime (tens to hundreds of rows) uses the 32x32x16 MFMA, which sustains about 1.5 times
+// the rate of the 16x16x32 one and needs half the B-operand bytes per flop.  Its A operand wants lane l to
+// hold row l % 32 and the 8 k-values of slot l / 32.  Two vertically adjacent re-tiled row-blocks (lane l:
+// row l % 16, k-group l / 16 of a 32-wide k-tile) hold two such operands - 32 weight rows with k-groups (0, 2)
+// and (1, 3) - each lane of which is a 16-byte piece of one of the two tiles, so they are loaded directly in
+// that order.  The activations are staged in LDS already split the same way: operand `op` of k-tile kt and
+// 32-row tile t holds, at lane l, X[32 t + l % 32][32 kt + 8 op + 16 (l / 32) ..+8] - a wave stores and later
+// reads a contiguous KiB.
+//
+// Eight waves, two per SIMD (a lone wave issues in order and leaves the matrix pipe idle while it issues
+// anything else): WN x WM of them, a wave owns RP pairs of row-blocks of W, streamed straight into a ring of U
+// register slots as above, and meets 32 NT rows of the workgroup's row tile.  Staging is double-buffered in chunks of KC k-tiles: the loads of chunk ch + 1 are
+// issued before the MFMAs of chunk ch and written to LDS after them.  The 1-D grid is decoded so that the row
+// tiles sharing a slice of W run on the same XCD at the same time (workgroup ids are dealt round-robin to the
+// 8 XCDs): W then comes from HBM once and from that L2 afterwards.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+// acc[p][t][e] = Y[m = m_base + 32 t + lane % 32][row 8 (e / 4) + 4 (lane / 32) + e % 4 of the 32 rows that
+// row-blocks rb0 + 2 p and rb0 + 2 p + 1 make]
+template <int NT, int RP, int EPI>
+__device__ __forceinline__ void mm_epilogue(const GemmArgs &g, floatx16 (&acc)[RP][NT], int m_base, int rb0, int split,
+                                            int slot, int lane) {
+    const int mj = lane & 31, h = lane >> 5;
     if (EPI == EPI_PARTIAL) {
-        float *out = g.Yp + (size_t)blockIdx.y * g.split_stride;
+        float *out = g.Yp + (size_t)split * g.split_stride;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int m = m_base + t * 16 + bj;
+            const int m = m_base + 32 * t + mj;
             if (m >= g.M) continue;
 #pragma unroll
-            for (int r = 0; r < RB; ++r) {
-                const int n = (rb0 + r) * 16 + bg * 4;
-                if (n + 3 < g.N && (g.N & 3) == 0) *reinterpret_cast<floatx4 *>(out + (size_t)m * g.N + n) = acc[r][t];
-                else
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < g.N) out[(size_t)m * g.N + n + e] = acc[r][t][e];
-            }
+            for (int p = 0; p < RP; ++p)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int n = (rb0 + 2 * p) * 16 + 8 * v + 4 * h;
+                    const floatx4 val = {acc[p][t][4 * v], acc[p][t][4 * v + 1], acc[p][t][4 * v + 2], acc[p][t][4 * v + 3]};
+                    if (n + 3 < g.N && (g.N & 3) == 0) *reinterpret_cast<floatx4 *>(out + (size_t)m * g.N + n) = val;
+                    else
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < g.N) out[(size_t)m * g.N + n + e] = val[e];
+                }
         }
     } else if (EPI == EPI_SWIGLU) {
-        // rows 0..7 of a block are gate, rows 8..15 up, of features 8 (rb0 + r) ..: lanes 32..63 hold the up
-        // values that lanes 0..31 need
+        // a row-block holds 8 gate rows over 8 up rows of the same features: this lane's registers 8 b + c and
+        // 8 b + 4 + c are gate and up of feature 8 (rb0 + 2 p + b) + 4 h + c
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int m = m_base + t * 16 + bj;
+            const int m = m_base + 32 * t + mj;
+            if (m >= g.M) continue;
 #pragma unroll
-            for (int r = 0; r < RB; ++r) {
-                floatx4 up;
+            for (int p = 0; p < RP; ++p)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) up[e] = __shfl_xor(acc[r][t][e], 32, 64);
-                if (bg < 2 && m < g.M) {
-                    const int f = (rb0 + r) * 8 + bg * 4;
+                for (int b = 0; b < 2; ++b) {
+                    const int f = (rb0 + 2 * p + b) * 8 + 4 * h;
+                    float hv[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float gt = acc[r][t][e];
-                        if (f + e < g.N) act_store(g.H, (size_t)m * g.N + f + e, gt / (1.0f + expf(-gt)) * up[e]);
+                        const float gt = acc[p][t][8 * b + e], up = acc[p][t][8 * b + 4 + e];
+                        hv[e] = gt / (1.0f + expf(-gt)) * up;
                     }
+                    if (f + 3 < g.N && (g.N & 3) == 0) act_store4(g.H, (size_t)m * g.N + f, hv[0], hv[1], hv[2], hv[3]);
+                    else
+                        for (int e = 0; e < 4; ++e)
+                            if (f + e < g.N) act_store(g.H, (size_t)m * g.N + f + e, hv[e]);
                 }
-            }
         }
-    } else {   // EPI_ARGMAX: best (value, lowest index) of this wave's 16*RB features for every row
+    } else {   // EPI_ARGMAX: best (value, lowest index) of this wave's 32 RP features for every row
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int m = m_base + t * 16 + bj;
+            const int m = m_base + 32 * t + mj;
             float best = -INFINITY;
             int idx = 0x7fffffff;
 #pragma unroll
-            for (int r = 0; r < RB; ++r)
+            for (int p = 0; p < RP; ++p)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int n = (rb0 + r) * 16 + bg * 4 + e;
-                    const float v = acc[r][t][e];
+                for (int e = 0; e < 16; ++e) {
+                    const int n = (rb0 + 2 * p) * 16 + 8 * (e / 4) + 4 * h + (e % 4);
+                    const float v = acc[p][t][e];
                     if (n < g.N) {
                         if (g.Yp && m < g.M) g.Yp[(size_t)m * g.N + n] = v;
                         if (v > best || (v == best && n < idx)) { best = v; idx = n; }
                     }
                 }
-#pragma unroll
-            for (int o = 16; o < 64; o <<= 1) {
-                const float ov = __shfl_xor(best, o, 64);
-                const int oi = __shfl_xor(idx, o, 64);
-                if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
-            }
-            if (bg == 0 && m < g.M) {
-                const int slot = blockIdx.x * WR + wr;   // one slot per row-block group
+            const float ov = __shfl_xor(best, 32, 64);
+            const int oi = __shfl_xor(idx, 32, 64);
+            if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+            if (h == 0 && m < g.M) {
                 g.cand_val[(size_t)m * g.n_cand + slot] = best;
                 g.cand_idx[(size_t)m * g.n_cand + slot] = idx;
             }
         }
     }
+}
+
+// NT: 32-row tiles per wave; WM: waves along the rows (8 / WM along the row-blocks); RP: pairs of row-blocks
+// per wave; KC: k-tiles per LDS chunk; U: register slots of the weight stream
+template <int NT, int WM, int RP, int KC, int U, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_mm(GemmArgs g) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    static_assert(KC % U == 0, "a chunk is a whole number of turns of the ring");
+    constexpr int NW = 8, WN = NW / WM, RB = 2 * RP;
+    constexpr int NTW = NT * WM;                          // 32-row tiles of the workgroup
+    constexpr int OPS = KC * NTW * 2;                     // B operands of one plane in a chunk
+    constexpr int PER_WAVE = (2 * OPS + NW - 1) / NW;     // operand loads a wave issues per chunk (both planes)
+    constexpr int BUF = 2 * OPS * 1024;                   // bytes of one chunk buffer
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave / WM, wm = wave % WM;
+    // ---- which (row-block group bx, k-split by, row tile z)
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int z = slot % g.gz, q = (slot / g.gz) * 8 + xcd;
+    if (q >= g.gx * g.gs) return;                         // the whole workgroup leaves: no barrier is reached
+    const int bx = q % g.gx, by = q / g.gx;
+    const int kt0 = by * g.kt_per_split;
+    const int ntile = min(g.kt_per_split, g.nkt - kt0);
+    const int rb0 = (bx * WN + wn) * RB;
+    const bool active = rb0 < g.nrb;                      // RB divides the padded number of row-blocks
+    const int m_base = z * (32 * NTW);
+
+    // A operands straight from the re-tiled W: lane l of operand `op` of pair p wants row l % 32 of the pair and
+    // k-group 2 (l / 32) + op, which row-block rb0 + 2 p + (l % 32) / 16 keeps at lane 16 (2 (l / 32) + op) + l % 16.
+    // A wave-wide load then reads four contiguous 256-byte runs, and the two operands of a pair together read
+    // both of its tiles exactly once.  Waves that differ only in wm stream the same row-blocks: the second one
+    // finds them in the vector L1.
+    const u32x4 *wp = g.Wt + ((size_t)((active ? rb0 : 0) + ((lane & 31) >> 4)) * g.nkt + kt0) * 64 + 32 * (lane >> 5) + (lane & 15);
+    const size_t wstep = (size_t)2 * g.nkt * 64;          // from one pair of row-blocks to the next
+    u32x4 abuf[U][RP][2];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int p = 0; p < RP; ++p)
+#pragma unroll
+            for (int op = 0; op < 2; ++op)   // a slot past the last k-tile re-reads that tile and is never used
+                abuf[u][p][op] = wp[p * wstep + (size_t)min(u, ntile - 1) * 64 + 16 * op];
+
+    floatx16 acc[RP][NT];
+#pragma unroll
+    for (int p = 0; p < RP; ++p)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[p][t][e] = 0.f;
+
+    // ---- staging: operand id i in [0, 2 OPS): plane i / OPS, then (k-tile, row tile, op) = ((i % OPS) / (2 NTW),
+    //      ((i % OPS) / 2) % NTW, i % 2); wave w takes ids w, w + NW, ...  No load is conditional (a branch would
+    //      make the compiler wait for each one at once): rows past M re-read row M - 1, k-tiles past the end
+    //      re-read the last one; neither is ever used.
+    static_assert((2 * OPS) % NW == 0, "every wave stages the same number of operands");
+    const int srow = m_base + (lane & 31);
+    const int scol = (lane >> 5) * 16;
+    u32x4 sreg[PER_WAVE];
+#define WISV_MM_STAGE_LOAD(ch)                                                                                     \
+    _Pragma("unroll") for (int j = 0; j < PER_WAVE; ++j) {                                                         \
+        const int i = wave + NW * j, pl = i / OPS, rem = i % OPS, lt = rem / (2 * NTW), t = (rem / 2) % NTW, op = rem & 1; \
+        const int kt = min((ch) * KC + lt, ntile - 1);                                                             \
+        const int row = min(srow + 32 * t, g.M - 1);                                                               \
+        sreg[j] = *reinterpret_cast<const u32x4 *>((pl ? g.Xlo : g.Xhi) + (size_t)row * g.kd +                     \
+                                                   (size_t)(kt0 + kt) * 32 + 8 * op + scol);                       \
+    }
+#define WISV_MM_STAGE_STORE(ch)                                                                                    \
+    _Pragma("unroll") for (int j = 0; j < PER_WAVE; ++j)                                                           \
+        *reinterpret_cast<u32x4 *>(lds + (size_t)((ch) & 1) * BUF + (size_t)(wave + NW * j) * 1024 + lane * 16) = sreg[j];
+    // A k-tile is four groups (op, plane) of NT B operands, each feeding NT RP independent MFMAs.  The B
+    // operands of group gi + 1 are read from LDS before the MFMAs of group gi issue (scheduling barriers keep
+    // that order): the LDS latency hides behind matrix work, the other wave of the SIMD fills what is left.
+#define WISV_MM_READ_B(gi, DST)                                                                                    \
+    _Pragma("unroll") for (int t = 0; t < NT; ++t)                                                                 \
+        DST[t] = *reinterpret_cast<const u32x4 *>(buf + ((((gi) & 1) * OPS) + ((((gi) >> 2) * NTW + t) * 2 + (((gi) >> 1) & 1))) * 1024);
+#define WISV_MM_GROUP(gi, A, SRC)                                                                                    \
+    _Pragma("unroll") for (int t = 0; t < NT; ++t) _Pragma("unroll") for (int p = 0; p < RP; ++p)                  \
+        acc[p][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8 *>(&A[p][((gi) >> 1) & 1]), \
+                                                           *reinterpret_cast<bf16x8 *>(&SRC[t]), acc[p][t], 0, 0, 0);
+    u32x4 bv[2][NT];
+
+    const int nchunk = (ntile + KC - 1) / KC;
+    WISV_MM_STAGE_LOAD(0)
+    WISV_MM_STAGE_STORE(0)
+    for (int ch = 0; ch < nchunk; ++ch) {
+        __syncthreads();   // chunk ch is in LDS; nobody still reads the buffer chunk ch + 1 goes to
+        // this wave's row tiles start at tile wm NT of the workgroup's
+        const unsigned char *buf = lds + (size_t)(ch & 1) * BUF + (size_t)(wm * NT) * 2048 + lane * 16;
+        const int kbase = ch * KC;
+        // the next chunk's activations are requested before this chunk's MFMAs and written to LDS after them; the
+        // write must wait for exactly these loads while the weight refills issued after them stay in flight, and
+        // the compiler can count those only if every path through the chunk issues the same number of loads
+        WISV_MM_STAGE_LOAD(ch + 1)
+#pragma unroll
+        for (int lt = 0; lt < KC; ++lt) {
+            if (kbase + lt < ntile) {   // uniform; no load inside, so the load counts below hold on every path
+                WISV_MM_READ_B(4 * lt, bv[0])
+#pragma unroll
+                for (int og = 0; og < 4; ++og) {
+                    if (og < 3) { WISV_MM_READ_B(4 * lt + og + 1, bv[(og + 1) & 1]) }
+                    __builtin_amdgcn_sched_barrier(0);
+                    WISV_MM_GROUP(4 * lt + og, abuf[lt % U], bv[og & 1])
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // refill the slot right after its use; past the end the last tile is re-read into a slot nobody uses
+#pragma unroll
+            for (int p = 0; p < RP; ++p)
+#pragma unroll
+                for (int op = 0; op < 2; ++op)
+                    abuf[lt % U][p][op] = wp[p * wstep + (size_t)min(kbase + lt + U, ntile - 1) * 64 + 16 * op];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        WISV_MM_STAGE_STORE(ch + 1)
+    }
+#undef WISV_MM_STAGE_LOAD
+#undef WISV_MM_STAGE_STORE
+#undef WISV_MM_READ_B
+#undef WISV_MM_GROUP
+    if (!active) return;
+    mm_epilogue<NT, RP, EPI>(g, acc, m_base + wm * (32 * NT), rb0, by, bx * WN + wn, lane);
 }
 
 // final argmax over the per-group candidates of every row
@@ -343,20 +570,41 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
     return true;
 }
 
-// More than 16 rows: a workgroup of eight waves shares one activation chunk in LDS (up to 128 rows, the
-// grid's z dimension walks further row tiles), two row-blocks per wave.
-template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits) {
-    const int nt = std::min(8, (g.M + 15) / 16);
-    switch (nt) {
-        case 2: return launch_ws_t<2, 2, 8, 1, 4, EPI>(c, g, splits, 72 * 1024);
-        case 3: return launch_ws_t<3, 2, 8, 1, 4, EPI>(c, g, splits, 72 * 1024);
-        case 4: return launch_ws_t<4, 2, 8, 1, 4, EPI>(c, g, splits, 100 * 1024);
-        case 5: return launch_ws_t<5, 2, 8, 1, 2, EPI>(c, g, splits, 100 * 1024);
-        case 6: return launch_ws_t<6, 2, 8, 1, 2, EPI>(c, g, splits, 100 * 1024);
-        case 7: return launch_ws_t<7, 2, 8, 1, 2, EPI>(c, g, splits, 140 * 1024);
-        case 8: return launch_ws_t<8, 2, 8, 1, 2, EPI>(c, g, splits, 140 * 1024);
-        default: return false;
+// More than 16 rows: k_gemm_mm.  Row tiles of 16 NT rows with the least padding, about one workgroup per CU.
+constexpr int MM_RP = 2;            // pairs of row-blocks per wave of k_gemm_mm
+constexpr int MM_RB = 2 * MM_RP;
+
+template <int NT, int WM, int KC, int U, int EPI>
+static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
+    constexpr int WN = 8 / WM, NTW = NT * WM;
+    g.gx = (g.nrb + WN * MM_RB - 1) / (WN * MM_RB);
+    g.gz = (g.M + 32 * NTW - 1) / (32 * NTW);
+    g.gs = splits;
+    const size_t lds = (size_t)2 * 2 * KC * NTW * 2 * 1024;   // two buffers, two planes, 2 operands per (k-tile, row tile)
+    static bool opted_in = false;     // per instantiation
+    if (lds > 64 * 1024 && !opted_in) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, MM_RP, KC, U, EPI>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return false;
+        opted_in = true;
     }
+    const unsigned grid = (unsigned)((g.gx * g.gs + 7) / 8 * 8 * g.gz);
+    hipLaunchKernelGGL((k_gemm_mm<NT, WM, MM_RP, KC, U, EPI>), dim3(grid), dim3(512), lds, c->stream, g);
+    return true;
+}
+
+// Row tiles of k_gemm_mm: up to 64 rows one tile met by all eight waves (each 64 weight rows), beyond that
+// tiles of 128 rows met by 4 x 2 waves.  Returns the number of row tiles and of row-blocks a workgroup covers.
+static int mm_shape(int rows, int *rb_per_wg) {
+    *rb_per_wg = rows <= 64 ? 8 * MM_RB : 4 * MM_RB;
+    return rows <= 64 ? 1 : (rows + 127) / 128;
+}
+
+// More than 16 rows: k_gemm_mm
+template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits) {
+    if (g.M <= 32) return launch_mm_t<1, 1, 2, 2, EPI>(c, g, splits);
+    if (g.M <= 64) return launch_mm_t<2, 1, 2, 2, EPI>(c, g, splits);
+    return launch_mm_t<2, 2, 2, 2, EPI>(c, g, splits);
 }
 
 bool ws_supported(const Ctx *c, int rows, int kd) {
@@ -384,10 +632,11 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
         s = (4096 + g.nrb - 1) / g.nrb;
         s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 8))));
     } else {
-        // at least ~512 workgroups of eight waves over (row-block groups) x (row tiles) x splits
-        const int wgs = (g.nrb / 16) * ((rows + 127) / 128);
-        s = (512 + wgs - 1) / std::max(1, wgs);
-        s = std::max(1, std::min(s, std::min(std::min(max_splits, 8), std::max(1, g.nkt / 16))));
+        // about one workgroup per CU over (row-block groups) x (row tiles) x splits; a split keeps >= 8 k-tiles
+        int rb_per_wg;
+        const int tiles = mm_shape(rows, &rb_per_wg);
+        const int base = ((g.nrb + rb_per_wg - 1) / rb_per_wg) * tiles;
+        s = std::max(1, std::min(256 / std::max(1, base), std::min(max_splits, std::max(1, g.nkt / 8))));
     }
     g.kt_per_split = (g.nkt + s - 1) / s;
     const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
@@ -418,7 +667,7 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     g.n_cand = g.nrb;                     // at most one candidate slot per row-block
     g.Yp = logits;
     g.cand_val = c->cand_val; g.cand_idx = c->cand_idx;
-    const int slots = rows <= 16 ? g.nrb : g.nrb / 2;
+    const int slots = rows <= 16 ? g.nrb : (g.nrb + MM_RB - 1) / MM_RB;
     {
         ProfScope ps(c, kclass);
         const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 8, EPI_ARGMAX>(c, g, 1, 70 * 1024)

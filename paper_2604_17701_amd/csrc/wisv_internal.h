@@ -63,6 +63,18 @@ __device__ __forceinline__ void act_store(const ActBuf &a, size_t i, float v) {
     a.lo[i] = l;
 }
 
+// four consecutive elements, i a multiple of 4: one 16-byte and two 8-byte stores
+__device__ __forceinline__ void act_store4(const ActBuf &a, size_t i, float v0, float v1, float v2, float v3) {
+    bf16_t h[4], l[4];
+    split2(v0, h[0], l[0]);
+    split2(v1, h[1], l[1]);
+    split2(v2, h[2], l[2]);
+    split2(v3, h[3], l[3]);
+    *reinterpret_cast<float4 *>(a.f + i) = make_float4(v0, v1, v2, v3);
+    *reinterpret_cast<uint2 *>(a.hi + i) = make_uint2(h[0] | ((unsigned)h[1] << 16), h[2] | ((unsigned)h[3] << 16));
+    *reinterpret_cast<uint2 *>(a.lo + i) = make_uint2(l[0] | ((unsigned)l[1] << 16), l[2] | ((unsigned)l[3] << 16));
+}
+
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
 enum KernelClass {
     KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_LMHEAD,
