@@ -65,6 +65,32 @@ def build_round(ctx, w, binding, gen, np, torch):
     return rnd, dict(drafts=drafts, hd=hd, row_map=row_map, csi=csi, tau=tau, pred_next=pred_next)
 
 
+def measured_traffic(workload, kclass):
+    """HBM bytes per launch (fetched + written) of the kernels of class `kclass`, from the committed rocprofv3
+    counter summary of this workload - or None when there is none or the kernel sources changed since."""
+    from paper_2604_17701_amd import profile_summary as ps
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, "no counter summary for this workload under profiles/"
+    sha, table = ps.read_traffic(path)
+    if sha != ps.source_hash():
+        return None, "kernel sources changed since the counters under profiles/ were taken"
+    epilogue = {"gemm_qkv_o_down": "0", "gemm_gate_up": "1", "lm_head": "2"}
+    launches = bytes_ = 0.0
+    for name, (n, fetch, write) in table.items():
+        base, args = ps.template_args(name)
+        if kclass == "attention":
+            hit = base == "k_attn_mfma"
+        else:
+            hit = base in ("k_gemm_ws", "k_gemm_mm") and args and args[-1] == epilogue.get(kclass)
+        if hit:
+            launches += n
+            bytes_ += n * (fetch + write)
+    if not launches:
+        return None, "the counter summary has no kernel of this class"
+    return bytes_ / launches, f"profiles/{workload}_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE scaled by a copy kernel)"
+
+
 def cpu_baseline(w, weights_dev, inputs, gen, np, torch, budget_s=20.0):
     """The oracle, as it stands, on the host cores: whole rounds of stream 0 of the same workload."""
     from oracle import wisv_oracle as wo
@@ -170,8 +196,9 @@ def main():
     k = kernels[dom]
     per_launch = alg_bytes[dom] / k["launches_per_round"]
     achieved = per_launch / (k["avg_us"] * 1e-6) / 1e9
+    traffic, traffic_note = measured_traffic(w.name, dom)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
                 "bytes_per_launch": per_launch, "avg_launch_us": k["avg_us"],
                 "event_pair_overhead_us": pair_us,
                 "timing": f"HIP event pair around every launch on the round's stream, {a.steps} rounds right after the timed ones, "

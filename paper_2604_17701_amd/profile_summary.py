@@ -71,6 +71,29 @@ def traffic(fetch_csv: str, write_csv: str, out: str, command: str):
                         f"write_bytes_per_launch {wr.get(k, 0.0) * cw:12.0f}\n")
 
 
+def read_traffic(path: str):
+    """Parses a traffic summary: (source hash, {kernel: (launches, fetch bytes, write bytes per launch)})."""
+    sha, table = None, {}
+    with open(path) as f:
+        for line in f:
+            if line.startswith("source_sha256"):
+                sha = line.split()[1]
+            elif line.startswith("kernel "):
+                body = line[len("kernel "):]
+                name = body[:body.index(" launches ")].strip()
+                nums = body[body.index(" launches "):].split()
+                table[name] = (int(nums[1]), float(nums[3]), float(nums[5]))
+    return sha, table
+
+
+def template_args(kernel: str):
+    """'k_gemm_ws<1, 1, 8, 1, 8, 1>' -> ('k_gemm_ws', ['1', '1', '8', '1', '8', '1'])"""
+    if "<" not in kernel:
+        return kernel, []
+    base, rest = kernel.split("<", 1)
+    return base, [a.strip() for a in rest.rstrip(">").split(",")]
+
+
 if __name__ == "__main__":
     if sys.argv[1] == "kernels":
         kernels(*sys.argv[2:5])
