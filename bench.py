@@ -36,8 +36,7 @@ def build_round(ctx, w, binding, gen, np, torch):
     for b in range(w.batch):
         for l in range(w.model.n_layers):
             k, v = gen.synthetic_kv(w, b, l, dev)
-            ctx._kv[l, b, 0, :, :w.ctx] = k
-            ctx._kv[l, b, 1, :, :w.ctx] = v
+            binding.kv_fill(ctx._kv, w.model, l, b, k, v)
         pn = gen.synthetic_pred_next(w, b)
         pred_next.append(pn)
         ctx.wisv_set_state(b, w.ctx, pn)
@@ -145,7 +144,7 @@ def main():
     wd = gen.make_weights(w.model, w.seed if a.config == 0 else configs.get(1).seed, dev)
     m = w.model
     max_ctx = w.ctx + w.k
-    kv = torch.zeros((m.n_layers, w.batch, 2, m.n_kv_heads, max_ctx, m.head_dim), dtype=gen.torch_dtype(m), device=dev)
+    kv = binding.new_kv_cache(m, w.batch, max_ctx, dev)
     ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
     rnd, inputs = build_round(ctx, w, binding, gen, np, torch)
     log(f"{w.name}: inputs resident after {time.time() - t0:.1f}s")

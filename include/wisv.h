@@ -87,7 +87,13 @@ typedef struct {
     int32_t device_id;
     void *hip_stream; /* hipStream_t all work is enqueued on (borrowed; NULL = the null stream) */
     void *kv_cache;   /* device pointer to borrowed cache memory, or NULL: the ctx allocates.
-                         Layout [n_layers][max_batch][2 (K,V)][n_kv_heads][max_ctx][head_dim], dtype as above */
+                         Layout [n_layers][max_batch][2 (K,V)][n_kv_heads] planes of ctx_pad * head_dim elements,
+                         ctx_pad = max_ctx rounded up to a multiple of 32, dtype as above.
+                         K plane: [ctx_pad][head_dim] (position-major).
+                         V plane: blocks of 32 positions, [ctx_pad / 32][head_dim][32]: element (pos, dim) sits at
+                         ((pos / 32) * head_dim + dim) * 32 + pos % 32, so that the attention kernel reads 32 cached
+                         values of one feature contiguously.  wisv_kv_import / wisv_kv_export convert from / to
+                         plain [n_kv_heads][len][head_dim] host arrays. */
     size_t kv_bytes;  /* size of kv_cache when borrowed (must cover the layout) */
 } wisv_config;
 

@@ -100,6 +100,29 @@ def load_library() -> C.CDLL:
     return _lib
 
 
+def ctx_pad(max_ctx: int) -> int:
+    """Positions per KV plane: max_ctx rounded up to a multiple of 32 (the V plane is stored in blocks of 32)."""
+    return (max_ctx + 31) // 32 * 32
+
+
+def new_kv_cache(model, max_batch: int, max_ctx: int, device) -> torch.Tensor:
+    """A zeroed cache tensor to lend to a Context: [n_layers][max_batch][2][n_kv_heads][ctx_pad * head_dim]."""
+    return torch.zeros((model.n_layers, max_batch, 2, model.n_kv_heads, ctx_pad(max_ctx) * model.head_dim),
+                       dtype=torch.float32 if model.dtype == "f32" else torch.bfloat16, device=device)
+
+
+def kv_fill(kv: torch.Tensor, model, layer: int, slot: int, k: torch.Tensor, v: torch.Tensor):
+    """Writes k, v ([n_kv_heads, len, head_dim], positions 0..len-1) into a tensor from new_kv_cache, in the
+    library's layout: K position-major, V in blocks of 32 positions with the feature index outside."""
+    g, n, hd = k.shape
+    cp = kv.shape[-1] // hd
+    kv[layer, slot, 0].view(g, cp, hd)[:, :n] = k
+    nb = (n + 31) // 32
+    vp = torch.zeros((g, nb * 32, hd), dtype=kv.dtype, device=kv.device)
+    vp[:, :n] = v
+    kv[layer, slot, 1].view(g, cp // 32, hd, 32)[:, :nb] = vp.view(g, nb, 32, hd).transpose(2, 3)
+
+
 def make_config(model, max_batch: int, max_ctx: int, max_k: int, device_id: int = 0, hip_stream: int = 0,
                 kv_cache: int = 0, kv_bytes: int = 0) -> wisv_config:
     """`model` carries the fields of wisv_inputs.configs.ModelShape (any object with those attributes)."""

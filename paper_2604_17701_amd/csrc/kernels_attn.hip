@@ -2,12 +2,16 @@
 // the K query rows of a stream x the query heads that share one KV head form one tile of up to 64 rows, so
 // every cached key/value byte is read once per (stream, KV head) and meets all of them.
 //
-// One workgroup = (k-split, KV head, stream).  Per 64-key chunk the four waves stage K and V through LDS
-// (coalesced 16-byte loads, rows padded against bank conflicts, next chunk prefetched into registers),
-// each wave takes 16 keys:  S^T = K Q^T on the 16x16x32 MFMA (queries fed as two bf16 terms), float online
-// softmax with wavefront reductions over the key dimension, then O^T += V^T P^T on the 16x16x16 MFMA
-// (probabilities fed as two bf16 terms, so P.V is exact to 2^-17).  Waves and k-splits are merged with the
-// usual (max, sum, unnormalised output) rule in a fixed order; a small kernel normalises.
+// One workgroup = (k-split, KV head, stream); its waves take steps of 32 keys round-robin and never meet before
+// the end: nothing is staged in LDS.  K rows go straight from the cache into the A operand of S^T = K Q^T
+// (16x16x32 MFMA, two tiles of 16 keys per step, queries as two bf16 terms in the B operand).  The keys of a
+// step are dealt to the two tiles so that lane group g ends up holding the scores of the eight consecutive keys
+// 8 g .. 8 g + 7 of every query: after the float online softmax these eight probabilities are, as they stand,
+// the B operand of O^T += V^T P^T on the 16x16x32 MFMA (two bf16 terms again, so P.V is exact to 2^-17), whose A
+// operand - 16 features x 32 keys of V^T - is one 16-byte load per lane from the cache's V plane, which keeps
+// 32 positions of a feature contiguous for exactly this reason.  Waves are merged through LDS at the end with
+// the usual (max, sum, unnormalised output) rule in wave order; k-splits, when there are several, by a small
+// kernel, otherwise the workgroup writes the attention output itself.
 #include <algorithm>
 
 #include "wisv_internal.h"
@@ -15,36 +19,61 @@
 namespace wisv {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int HD = 128, CHUNK = 64, PITCH = 272;            // bytes per staged row: 256 + 16
-constexpr int BUF_BYTES = 2 * CHUNK * PITCH;                // K rows then V rows of one chunk
+constexpr int HD = 128, STEP = 32;
 
 struct AttnArgs {
     const float *q;           // rotated queries [rows][H * 128]
-    const bf16_t *kv_layer;   // this layer's cache: [slot][K|V][G][max_ctx][128]
+    const bf16_t *kv_layer;   // this layer's cache: [slot][K|V][G] planes of ctx_pad * 128
     size_t slot_stride;       // elements per slot
-    int H, G, rep, K, max_ctx, n_splits, rows;
+    int H, G, rep, K, max_ctx, ctx_pad, n_splits, rows;
     const int32_t *row_slot, *row_pos;
-    float *po, *pm, *pl;      // partials [split][rows][H][128], [split][rows][H]
+    float *po, *pm, *pl;      // partials [split][rows][H][128], [split][rows][H]  (n_splits > 1)
+    ActBuf o;                 // attention output [rows][H][128]                    (n_splits == 1)
 };
 
-template <int NQ>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
+// NQ: 16-row query tiles; NW: waves per workgroup
+template <int NQ, int NW>
+__global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, bj = lane & 15, bg = lane >> 4;
     const int m0 = b * a.K;
     const int L = a.row_pos[m0], slot = a.row_slot[m0];
     const int n_keys = min(L + a.K, a.max_ctx), R = a.rep * a.K;
-    const bf16_t *kc = a.kv_layer + (size_t)slot * a.slot_stride + (size_t)g * a.max_ctx * HD;
-    const bf16_t *vc = kc + (size_t)a.G * a.max_ctx * HD;
-    const int n_chunks = (n_keys + CHUNK - 1) / CHUNK, cps = (n_chunks + a.n_splits - 1) / a.n_splits;
-    const int c_begin = split * cps, c_end = min(n_chunks, c_begin + cps);
+    const bf16_t *kc = a.kv_layer + (size_t)slot * a.slot_stride + (size_t)g * a.ctx_pad * HD;
+    const bf16_t *vc = kc + (size_t)a.G * a.ctx_pad * HD;
+    const int n_steps = (n_keys + STEP - 1) / STEP, sps = (n_steps + a.n_splits - 1) / a.n_splits;
+    const int s_begin = split * sps, s_end = min(n_steps, s_begin + sps);
+
+    // ---- the first step's loads go out before anything else.  Lane (bj, bg): tile A row bj is key
+    //      8 (bj / 4) + bj % 4 of the step, tile B row bj the key four further; V^T row bj of feature tile dt.
+    u32x4 ka[4], kb[4], va[8];
+    const int krow = 8 * (bj >> 2) + (bj & 3);
+#define WISV_ATTN_LOAD_K(s_)                                                                              \
+    {                                                                                                     \
+        const bf16_t *pa_ = kc + (size_t)min((s_) * STEP + krow, n_keys - 1) * HD + 8 * bg;               \
+        const bf16_t *pb_ = kc + (size_t)min((s_) * STEP + krow + 4, n_keys - 1) * HD + 8 * bg;           \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                   \
+            ka[t] = *reinterpret_cast<const u32x4 *>(pa_ + 32 * t);                                       \
+            kb[t] = *reinterpret_cast<const u32x4 *>(pb_ + 32 * t);                                       \
+        }                                                                                                 \
+    }
+#define WISV_ATTN_LOAD_V(s_)                                                                              \
+    {                                                                                                     \
+        const bf16_t *pv_ = vc + ((size_t)(s_) * HD + bj) * STEP + 8 * bg;                                \
+        _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) va[dt] = *reinterpret_cast<const u32x4 *>(pv_ + (size_t)dt * 16 * STEP); \
+    }
+    int s = s_begin + wave;
+    if (s < s_end) {
+        WISV_ATTN_LOAD_K(s)
+        WISV_ATTN_LOAD_V(s)
+    }
 
     // ---- queries as MFMA B operands (two bf16 terms): lane (bj, bg) holds Q[rho = 16 nq + bj][32 t + 8 bg ..]
-    uint4 qhi[NQ][4], qlo[NQ][4];
+    u32x4 qhi[NQ][4], qlo[NQ][4];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         const int rho = nq * 16 + bj;
@@ -66,8 +95,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
                     l[e] = l0 | ((uint32_t)l1 << 16);
                 }
             }
-            qhi[nq][t] = make_uint4(h[0], h[1], h[2], h[3]);
-            qlo[nq][t] = make_uint4(l[0], l[1], l[2], l[3]);
+            qhi[nq][t] = u32x4{h[0], h[1], h[2], h[3]};
+            qlo[nq][t] = u32x4{l[0], l[1], l[2], l[3]};
         }
     }
 
@@ -81,158 +110,147 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
         for (int dt = 0; dt < 8; ++dt) oacc[nq][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- chunk loop.  Thread tid moves 16-byte segment `seg` of staged rows krow, krow + 16, krow + 32, krow + 48
-    //      of the chunk's K and V.
-    // (named registers rather than arrays: the prefetched chunk must stay in VGPRs across the loop)
-    uint4 k0, k1, k2, k3, v0, v1, v2, v3;
-    const int seg = tid & 15, krow = tid >> 4;               // segment i covers staged row krow + 16 i
-#define WISV_ATTN_LOAD(c_, i_, kr_, vr_)                                                      \
-    {                                                                                         \
-        const int key_ = min((c_) * CHUNK + krow + 16 * (i_), n_keys - 1);                    \
-        kr_ = *reinterpret_cast<const uint4 *>(kc + (size_t)key_ * HD + seg * 8);             \
-        vr_ = *reinterpret_cast<const uint4 *>(vc + (size_t)key_ * HD + seg * 8);             \
-    }
-#define WISV_ATTN_FETCH(c_)          \
-    WISV_ATTN_LOAD(c_, 0, k0, v0)    \
-    WISV_ATTN_LOAD(c_, 1, k1, v1)    \
-    WISV_ATTN_LOAD(c_, 2, k2, v2)    \
-    WISV_ATTN_LOAD(c_, 3, k3, v3)
-#define WISV_ATTN_PUT(i_, kr_, vr_)                                                                        \
-    *reinterpret_cast<uint4 *>(buf + (krow + 16 * (i_)) * PITCH + seg * 16) = kr_;                         \
-    *reinterpret_cast<uint4 *>(buf + CHUNK * PITCH + (krow + 16 * (i_)) * PITCH + seg * 16) = vr_;
     const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
-    if (c_begin < c_end) { WISV_ATTN_FETCH(c_begin) }
-    for (int c = c_begin; c < c_end; ++c) {
-        unsigned char *buf = lds + (size_t)((c - c_begin) & 1) * BUF_BYTES;
-        WISV_ATTN_PUT(0, k0, v0)
-        WISV_ATTN_PUT(1, k1, v1)
-        WISV_ATTN_PUT(2, k2, v2)
-        WISV_ATTN_PUT(3, k3, v3)
-        __syncthreads();   // chunk c staged; the other buffer is free (everyone finished chunk c - 1)
-        if (c + 1 < c_end) { WISV_ATTN_FETCH(c + 1) }
-        const unsigned char *kb = buf + (16 * wave) * PITCH, *vb = buf + CHUNK * PITCH + (16 * wave) * PITCH;
-        const int kbase = c * CHUNK + 16 * wave;
-        if (kbase >= n_keys) continue;
-
-        // S^T tile: rows = 16 keys (A operand from LDS), columns = 16 queries
-        uint4 ka[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) ka[t] = *reinterpret_cast<const uint4 *>(kb + bj * PITCH + (32 * t + 8 * bg) * 2);
-        uint2 phi[NQ], plo[NQ];
+    for (; s < s_end; s += NW) {
+        const int kbase = s * STEP + 8 * bg;     // this lane's eight keys: kbase .. kbase + 7
+        const bool more = s + NW < s_end;
+        u32x4 phi[NQ], plo[NQ];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
-            floatx4 s = {0.f, 0.f, 0.f, 0.f};
+            floatx4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]),
-                                                            *reinterpret_cast<bf16x8 *>(&qhi[nq][t]), s, 0, 0, 0);
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]),
-                                                            *reinterpret_cast<bf16x8 *>(&qlo[nq][t]), s, 0, 0, 0);
+                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]),
+                                                             *reinterpret_cast<bf16x8 *>(&qhi[nq][t]), sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&kb[t]),
+                                                             *reinterpret_cast<bf16x8 *>(&qhi[nq][t]), sb, 0, 0, 0);
+                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]),
+                                                             *reinterpret_cast<bf16x8 *>(&qlo[nq][t]), sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&kb[t]),
+                                                             *reinterpret_cast<bf16x8 *>(&qlo[nq][t]), sb, 0, 0, 0);
             }
-            // lane holds keys kbase + 4 bg + r (r = 0..3) of query rho = 16 nq + bj
+            // lane holds keys kbase + e (e = 0..3 from tile A, 4..7 from tile B) of query rho = 16 nq + bj
             const int rho = nq * 16 + bj;
             const int qpos = L + rho / a.rep;
-            float sv[4], mx = -INFINITY;
+            float sv[8], mx = -INFINITY;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int kp = kbase + 4 * bg + r;
-                sv[r] = (rho < R && kp <= qpos && kp < n_keys) ? s[r] * scale : -INFINITY;
-                mx = fmaxf(mx, sv[r]);
+            for (int e = 0; e < 8; ++e) {
+                const int kp = kbase + e;
+                const float x = e < 4 ? sa[e] : sb[e - 4];
+                sv[e] = (rho < R && kp <= qpos && kp < n_keys) ? x * scale : -INFINITY;
+                mx = fmaxf(mx, sv[e]);
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m_run[nq], mx);
-            float alpha = 1.f, p[4] = {0.f, 0.f, 0.f, 0.f};
+            float alpha = 1.f, p[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             if (m_new != -INFINITY) {
                 alpha = m_run[nq] == -INFINITY ? 0.f : expf(m_run[nq] - m_new);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) p[r] = sv[r] == -INFINITY ? 0.f : expf(sv[r] - m_new);
+                for (int e = 0; e < 8; ++e) p[e] = sv[e] == -INFINITY ? 0.f : expf(sv[e] - m_new);
             }
-            l_run[nq] = l_run[nq] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+            l_run[nq] = l_run[nq] * alpha + (((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7])));
             m_run[nq] = m_new;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) oacc[nq][dt] *= alpha;
-            bf16_t h[4], l[4];
+            uint32_t h[4], l[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) split2(p[r], h[r], l[r]);
-            phi[nq] = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
-            plo[nq] = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+            for (int e = 0; e < 4; ++e) {
+                bf16_t h0, l0, h1, l1;
+                split2(p[2 * e], h0, l0);
+                split2(p[2 * e + 1], h1, l1);
+                h[e] = h0 | ((uint32_t)h1 << 16);
+                l[e] = l0 | ((uint32_t)l1 << 16);
+            }
+            phi[nq] = u32x4{h[0], h[1], h[2], h[3]};
+            plo[nq] = u32x4{l[0], l[1], l[2], l[3]};
         }
-        // O^T tiles: rows = 16 features (A operand = V^T gathered from LDS), columns = 16 queries, k = 16 keys
+        // the K registers are free: request the next step's keys
+        if (more) { WISV_ATTN_LOAD_K(s + NW) }
+        // positions past the end of the sequence may hold anything (0 x NaN would poison the sum): clear them
+        if (s * STEP + STEP > n_keys) {
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t keep = (kbase + 2 * e < n_keys ? 0xffffu : 0u) | (kbase + 2 * e + 1 < n_keys ? 0xffff0000u : 0u);
+                    va[dt][e] &= keep;
+                }
+        }
+        // O^T tiles: rows = 16 features (A operand = V^T), columns = 16 queries, k = this lane group's 8 keys
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            uint16_t v[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = *reinterpret_cast<const uint16_t *>(vb + (4 * bg + e) * PITCH + (16 * dt + bj) * 2);
-            uint2 va = make_uint2(v[0] | ((uint32_t)v[1] << 16), v[2] | ((uint32_t)v[3] << 16));
 #pragma unroll
             for (int nq = 0; nq < NQ; ++nq) {
-                oacc[nq][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<s16x4 *>(&va),
-                                                                        *reinterpret_cast<s16x4 *>(&phi[nq]), oacc[nq][dt], 0, 0, 0);
-                oacc[nq][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<s16x4 *>(&va),
-                                                                        *reinterpret_cast<s16x4 *>(&plo[nq]), oacc[nq][dt], 0, 0, 0);
+                oacc[nq][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&va[dt]),
+                                                                      *reinterpret_cast<bf16x8 *>(&phi[nq]), oacc[nq][dt], 0, 0, 0);
+                oacc[nq][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&va[dt]),
+                                                                      *reinterpret_cast<bf16x8 *>(&plo[nq]), oacc[nq][dt], 0, 0, 0);
             }
         }
+        if (more) { WISV_ATTN_LOAD_V(s + NW) }
     }
+#undef WISV_ATTN_LOAD_K
+#undef WISV_ATTN_LOAD_V
 
-#undef WISV_ATTN_FETCH
-#undef WISV_ATTN_LOAD
-#undef WISV_ATTN_PUT
-
-    // ---- sums over the four lane groups (each held the keys 4 bg + r of every tile), fixed order
+    // ---- sums over the four lane groups (each held eight keys of every step), fixed order
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         const float l1 = l_run[nq] + __shfl_xor(l_run[nq], 16, 64);
         l_run[nq] = l1 + __shfl_xor(l1, 32, 64);
     }
 
-    // ---- merge waves 1..3 into wave 0 through LDS, one at a time.  Layout of one wave's state:
-    //      [nq][dt][lane] floatx4, then m[nq][lane], l[nq][lane]
-    floatx4 *so = reinterpret_cast<floatx4 *>(lds);
-    float *sm = reinterpret_cast<float *>(lds) + NQ * 8 * 64 * 4, *sl = sm + NQ * 64;
-    for (int w = 1; w < 4; ++w) {
-        __syncthreads();
-        if (wave == w) {
+    // ---- merge the waves.  Every wave publishes (m, l) of its queries, rescales its output to the common
+    //      maximum and publishes that too; wave w then adds up feature tiles w, w + NW, .. of all waves in
+    //      wave order.  LDS: sm, sl [NW][NQ][16] floats, then so [NW][NQ][8][64] floatx4.
+    float *sm = reinterpret_cast<float *>(lds), *sl = sm + NW * NQ * 16;
+    floatx4 *so = reinterpret_cast<floatx4 *>(sl + NW * NQ * 16);
+    if (bg == 0) {
 #pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) {
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) so[(nq * 8 + dt) * 64 + lane] = oacc[nq][dt];
-                sm[nq * 64 + lane] = m_run[nq];
-                sl[nq * 64 + lane] = l_run[nq];
-            }
-        }
-        __syncthreads();
-        if (wave == 0) {
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) {
-                const float mw = sm[nq * 64 + lane], lw = sl[nq * 64 + lane];
-                const float m_new = fmaxf(m_run[nq], mw);
-                float a0 = 1.f, aw = 0.f;
-                if (m_new != -INFINITY) {
-                    a0 = m_run[nq] == -INFINITY ? 0.f : expf(m_run[nq] - m_new);
-                    aw = mw == -INFINITY ? 0.f : expf(mw - m_new);
-                }
-                l_run[nq] = l_run[nq] * a0 + lw * aw;
-                m_run[nq] = m_new;
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) oacc[nq][dt] = oacc[nq][dt] * a0 + so[(nq * 8 + dt) * 64 + lane] * aw;
-            }
+        for (int nq = 0; nq < NQ; ++nq) {
+            sm[(wave * NQ + nq) * 16 + bj] = m_run[nq];
+            sl[(wave * NQ + nq) * 16 + bj] = l_run[nq];
         }
     }
-    if (wave != 0) return;
-
-    // ---- this split's partial: lane holds features 16 dt + 4 bg + r of query rho = 16 nq + bj
+    __syncthreads();
+    float m_all[NQ], l_all[NQ];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-        const int rho = nq * 16 + bj;
-        if (rho >= R) continue;
-        const size_t row = ((size_t)split * a.rows + m0 + rho / a.rep) * a.H + (size_t)g * a.rep + rho % a.rep;
-        if (bg == 0) {
-            a.pm[row] = m_run[nq];
-            a.pl[row] = l_run[nq];
+        float mx = -INFINITY;
+        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm[(w * NQ + nq) * 16 + bj]);
+        float ls = 0.f;
+        for (int w = 0; w < NW; ++w) {
+            const float mw = sm[(w * NQ + nq) * 16 + bj];
+            if (mw != -INFINITY) ls += sl[(w * NQ + nq) * 16 + bj] * expf(mw - mx);
         }
+        m_all[nq] = mx;
+        l_all[nq] = ls;
+        const float mine = m_run[nq] == -INFINITY ? 0.f : expf(m_run[nq] - mx);
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<floatx4 *>(a.po + row * HD + 16 * dt + 4 * bg) = oacc[nq][dt];
+        for (int dt = 0; dt < 8; ++dt) so[((wave * NQ + nq) * 8 + dt) * 64 + lane] = oacc[nq][dt] * mine;
+    }
+    __syncthreads();
+    for (int dt = wave; dt < 8; dt += NW) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            const int rho = nq * 16 + bj;
+            floatx4 acc = so[((0 * NQ + nq) * 8 + dt) * 64 + lane];
+            for (int w = 1; w < NW; ++w) acc += so[((w * NQ + nq) * 8 + dt) * 64 + lane];
+            if (rho >= R) continue;
+            // lane holds features 16 dt + 4 bg + r of query rho
+            const int m = m0 + rho / a.rep, h = g * a.rep + rho % a.rep;
+            if (a.n_splits == 1) {
+                const float inv = 1.0f / l_all[nq];
+                act_store4(a.o, ((size_t)m * a.H + h) * HD + 16 * dt + 4 * bg, acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+            } else {
+                const size_t row = ((size_t)split * a.rows + m) * a.H + h;
+                *reinterpret_cast<floatx4 *>(a.po + row * HD + 16 * dt + 4 * bg) = acc;
+                if (dt == 0 && bg == 0) {
+                    a.pm[row] = m_all[nq];
+                    a.pl[row] = l_all[nq];
+                }
+            }
+        }
     }
 }
 
@@ -254,16 +272,16 @@ __global__ void k_attn_combine(const float *__restrict__ po, const float *__rest
     act_store(o, ((size_t)m * H + h) * HD + d, num / den);
 }
 
-template <int NQ> static bool launch_nq(Ctx *c, const AttnArgs &a, dim3 grid) {
+template <int NQ, int NW> static bool launch_nq(Ctx *c, const AttnArgs &a, dim3 grid) {
+    const size_t lds = (size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16);
     static bool opted_in = false;
-    if (!opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_mfma<NQ>), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (lds > 64 * 1024 && !opted_in) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_mfma<NQ, NW>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 160 * 1024) != hipSuccess)
             return false;
         opted_in = true;
     }
-    const size_t merge = (size_t)NQ * (8 * 64 * 16 + 2 * 64 * 4);
-    hipLaunchKernelGGL(k_attn_mfma<NQ>, grid, dim3(256), std::max<size_t>(2 * BUF_BYTES, merge), c->stream, a);
+    hipLaunchKernelGGL((k_attn_mfma<NQ, NW>), grid, dim3(64 * NW), lds, c->stream, a);
     return true;
 }
 
@@ -274,27 +292,30 @@ bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer) {
     AttnArgs a;
     a.q = c->q;
     a.kv_layer = (const bf16_t *)kv_ptr(c, layer, 0, 0);
-    a.slot_stride = (size_t)2 * g.n_kv_heads * g.max_ctx * g.head_dim;
-    a.H = g.n_heads; a.G = g.n_kv_heads; a.rep = rep; a.K = f.k; a.max_ctx = g.max_ctx; a.rows = f.rows;
+    a.slot_stride = (size_t)2 * g.n_kv_heads * c->ctx_pad * g.head_dim;
+    a.H = g.n_heads; a.G = g.n_kv_heads; a.rep = rep; a.K = f.k; a.max_ctx = g.max_ctx; a.ctx_pad = c->ctx_pad; a.rows = f.rows;
     a.row_slot = c->row_slot; a.row_pos = c->row_pos;
     a.po = c->att_o; a.pm = c->att_m; a.pl = c->att_l;
-    // enough workgroups to cover the chip twice, at least two 64-key chunks per split
-    const int n_chunks = (f.max_len_ub + CHUNK - 1) / CHUNK;
-    const int want = (512 + f.batch * g.n_kv_heads - 1) / (f.batch * g.n_kv_heads);
-    a.n_splits = std::max(1, std::min(std::min(want, (n_chunks + 1) / 2), c->att_max_splits));
+    a.o = c->o;
+    // One workgroup per (stream, KV head) when that fills the chip or the context is short (then the workgroup
+    // writes the output itself); otherwise k-splits of at least four 32-key steps per wave
+    const int nw = R <= 32 ? 8 : 4;
+    const int n_steps = (f.max_len_ub + STEP - 1) / STEP, wgs = f.batch * g.n_kv_heads;
+    int want = wgs >= 256 ? 1 : std::min((512 + wgs - 1) / wgs, (n_steps + 4 * nw - 1) / (4 * nw));
+    a.n_splits = std::max(1, std::min(want, c->att_max_splits));
     dim3 grid(a.n_splits, g.n_kv_heads, f.batch);
     {
         ProfScope ps(c, KC_ATTN);
         bool ok;
         switch ((R + 15) / 16) {
-            case 1: ok = launch_nq<1>(c, a, grid); break;
-            case 2: ok = launch_nq<2>(c, a, grid); break;
-            case 3: ok = launch_nq<3>(c, a, grid); break;
-            default: ok = launch_nq<4>(c, a, grid); break;
+            case 1: ok = launch_nq<1, 8>(c, a, grid); break;
+            case 2: ok = launch_nq<2, 8>(c, a, grid); break;
+            case 3: ok = launch_nq<3, 4>(c, a, grid); break;
+            default: ok = launch_nq<4, 4>(c, a, grid); break;
         }
         if (!ok) return false;
     }
-    {
+    if (a.n_splits > 1) {
         ProfScope ps(c, KC_ATTN_COMBINE);
         hipLaunchKernelGGL(k_attn_combine, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
                            a.n_splits, f.rows, g.n_heads, c->o);

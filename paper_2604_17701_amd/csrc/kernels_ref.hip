@@ -183,7 +183,7 @@ void launch_gemm_ref(Ctx *c, const float *A, const void *W, float *Y, int rows, 
 template <typename WT, typename AT>
 __global__ void k_rope_append(const float *__restrict__ qkv, int n_partial, size_t partial_stride, int H, int G, int hd, const int32_t *__restrict__ row_slot,
                               const int32_t *__restrict__ row_pos, const float *__restrict__ cs,
-                              const float *__restrict__ sn, AT *q_out, WT *kv_layer, size_t slot_stride, int max_ctx) {
+                              const float *__restrict__ sn, AT *q_out, WT *kv_layer, size_t slot_stride, int ctx_pad) {
     const int m = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     const int d_q = H * hd, d_kv = G * hd, pos = row_pos[m];
     const float *src = qkv + (size_t)m * (d_q + 2 * d_kv) + (size_t)hh * hd;
@@ -198,14 +198,13 @@ __global__ void k_rope_append(const float *__restrict__ qkv, int n_partial, size
         Elem<AT>::store(dst + i, a * co - b * si);
         Elem<AT>::store(dst + i + half, b * co + a * si);
     } else if (hh < H + G) {
-        WT *dst = kv_layer + (size_t)row_slot[m] * slot_stride + ((size_t)(hh - H) * max_ctx + pos) * hd;
+        WT *dst = kv_layer + (size_t)row_slot[m] * slot_stride + ((size_t)(hh - H) * ctx_pad + pos) * hd;
         Elem<WT>::store(dst + i, a * co - b * si);
         Elem<WT>::store(dst + i + half, b * co + a * si);
     } else {
-        WT *dst = kv_layer + (size_t)row_slot[m] * slot_stride + (size_t)G * max_ctx * hd +
-                  ((size_t)(hh - H - G) * max_ctx + pos) * hd;
-        Elem<WT>::store(dst + i, a);
-        Elem<WT>::store(dst + i + half, b);
+        WT *dst = kv_layer + (size_t)row_slot[m] * slot_stride + (size_t)(hh - H) * ctx_pad * hd;   // V planes follow the G K planes
+        Elem<WT>::store(dst + v_plane_index(pos, i, hd), a);
+        Elem<WT>::store(dst + v_plane_index(pos, i + half, hd), b);
     }
 }
 
@@ -213,24 +212,24 @@ void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial) {
     const size_t pstride = (size_t)c->rows_max * c->d_qkv;
     ProfScope ps(c, KC_ROPE);
     const wisv_config &g = c->cfg;
-    const size_t slot_stride = (size_t)2 * g.n_kv_heads * g.max_ctx * g.head_dim;
+    const size_t slot_stride = (size_t)2 * g.n_kv_heads * c->ctx_pad * g.head_dim;
     dim3 grid(f.rows, g.n_heads + 2 * g.n_kv_heads), block(g.head_dim / 2);
     void *kvl = kv_ptr(c, layer, 0, 0);
     if (c->bf16)
         hipLaunchKernelGGL((k_rope_append<bf16_t, float>), grid, block, 0, c->stream, c->qkv, n_partial, pstride, g.n_heads, g.n_kv_heads,
                            g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, c->q, (bf16_t *)kvl,
-                           slot_stride, g.max_ctx);
+                           slot_stride, c->ctx_pad);
     else
         hipLaunchKernelGGL((k_rope_append<float, float>), grid, block, 0, c->stream, c->qkv, n_partial, pstride, g.n_heads, g.n_kv_heads,
                            g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, c->q, (float *)kvl,
-                           slot_stride, g.max_ctx);
+                           slot_stride, c->ctx_pad);
 }
 
 // ------------------------------------------------------------------------------------------ attention (fallback)
 // one block per (row, query head): scores of the visible keys in LDS, float softmax, then P.V
 template <typename WT, typename AT>
 __global__ void k_attn_ref(const AT *__restrict__ q, const WT *__restrict__ kv_layer, size_t slot_stride, int H, int G,
-                           int hd, int max_ctx, const int32_t *__restrict__ row_slot,
+                           int hd, int ctx_pad, const int32_t *__restrict__ row_slot,
                            const int32_t *__restrict__ row_pos, ActBuf o) {
     extern __shared__ float smem[];
     float *qs = smem;            // [hd]
@@ -238,8 +237,8 @@ __global__ void k_attn_ref(const AT *__restrict__ q, const WT *__restrict__ kv_l
     float *sc = red + 260;       // [n_vis]
     const int m = blockIdx.x, h = blockIdx.y, g = h / (H / G), tid = threadIdx.x;
     const int n_vis = row_pos[m] + 1;
-    const WT *kc = kv_layer + (size_t)row_slot[m] * slot_stride + (size_t)g * max_ctx * hd;
-    const WT *vc = kc + (size_t)G * max_ctx * hd;
+    const WT *kc = kv_layer + (size_t)row_slot[m] * slot_stride + (size_t)g * ctx_pad * hd;
+    const WT *vc = kc + (size_t)G * ctx_pad * hd;
     if (tid < hd) qs[tid] = Elem<AT>::load(q + (size_t)m * H * hd + (size_t)h * hd + tid);
     __syncthreads();
     const float scale = 1.0f / sqrtf((float)hd);
@@ -265,7 +264,7 @@ __global__ void k_attn_ref(const AT *__restrict__ q, const WT *__restrict__ kv_l
     sum = block_sum<256>(sum, red + 256);   // also makes every sc[] visible
     const int dim = tid % hd, part = tid / hd, nparts = 256 / hd;
     float acc = 0.f;
-    for (int s = part; s < n_vis; s += nparts) acc = fmaf(sc[s], Elem<WT>::load(vc + (size_t)s * hd + dim), acc);
+    for (int s = part; s < n_vis; s += nparts) acc = fmaf(sc[s], Elem<WT>::load(vc + v_plane_index(s, dim, hd)), acc);
     red[tid] = acc;
     __syncthreads();
     if (part == 0) {
@@ -277,18 +276,42 @@ __global__ void k_attn_ref(const AT *__restrict__ q, const WT *__restrict__ kv_l
 void launch_attn_ref(Ctx *c, const Fwd &f, int layer) {
     ProfScope ps(c, KC_ATTN);
     const wisv_config &g = c->cfg;
-    const size_t slot_stride = (size_t)2 * g.n_kv_heads * g.max_ctx * g.head_dim;
+    const size_t slot_stride = (size_t)2 * g.n_kv_heads * c->ctx_pad * g.head_dim;
     const size_t lds = sizeof(float) * (g.head_dim + 260 + f.max_len_ub);
     dim3 grid(f.rows, g.n_heads);
     void *kvl = kv_ptr(c, layer, 0, 0);
     if (c->bf16)
         hipLaunchKernelGGL((k_attn_ref<bf16_t, float>), grid, dim3(256), lds, c->stream, (const float *)c->q,
-                           (const bf16_t *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, g.max_ctx,
+                           (const bf16_t *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, c->ctx_pad,
                            c->row_slot, c->row_pos, c->o);
     else
         hipLaunchKernelGGL((k_attn_ref<float, float>), grid, dim3(256), lds, c->stream, (const float *)c->q,
-                           (const float *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, g.max_ctx, c->row_slot,
+                           (const float *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, c->ctx_pad, c->row_slot,
                            c->row_pos, c->o);
+}
+
+// ------------------------------------------------------------------------------------------ V plane <-> rows
+// rows: [G][len][hd] (what the host hands over); plane: one (layer, slot) V plane [G][ctx_pad / 32][hd][32]
+template <typename WT>
+__global__ void k_v_reblock(WT *rows, WT *plane, int len, int hd, int ctx_pad, bool to_plane) {
+    const int g = blockIdx.y;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)len * hd) return;
+    const int pos = i / hd, dim = i % hd;
+    WT *r = rows + ((size_t)g * len + pos) * hd + dim, *q = plane + (size_t)g * ctx_pad * hd + v_plane_index(pos, dim, hd);
+    if (to_plane) *q = *r;
+    else *r = *q;
+}
+
+void launch_v_reblock(Ctx *c, void *rows, void *plane, int len, bool to_plane) {
+    const wisv_config &g = c->cfg;
+    dim3 grid((unsigned)(((size_t)len * g.head_dim + 255) / 256), g.n_kv_heads);
+    if (c->bf16)
+        hipLaunchKernelGGL(k_v_reblock<bf16_t>, grid, dim3(256), 0, c->stream, (bf16_t *)rows, (bf16_t *)plane, len, g.head_dim,
+                           c->ctx_pad, to_plane);
+    else
+        hipLaunchKernelGGL(k_v_reblock<float>, grid, dim3(256), 0, c->stream, (float *)rows, (float *)plane, len, g.head_dim,
+                           c->ctx_pad, to_plane);
 }
 
 // ------------------------------------------------------------------------------------------ SwiGLU

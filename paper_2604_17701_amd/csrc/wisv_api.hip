@@ -18,7 +18,7 @@ namespace wisv {
 
 void *kv_ptr(const Ctx *c, int layer, int slot, int which) {
     const wisv_config &g = c->cfg;
-    const size_t half = (size_t)g.n_kv_heads * g.max_ctx * g.head_dim;
+    const size_t half = (size_t)g.n_kv_heads * c->ctx_pad * g.head_dim;
     const size_t off = (((size_t)layer * g.max_batch + slot) * 2 + which) * half;
     return (char *)c->kv + off * c->esz;
 }
@@ -80,7 +80,8 @@ static const char *check_config(const wisv_config *g) {
     if (g->max_ctx <= g->max_k || g->max_ctx > (1 << 20)) return "max_ctx must exceed max_k (and be at most 2^20)";
     if (g->device_id < 0) return "device_id is negative";
     const size_t esz = g->dtype == WISV_BF16 ? 2 : 4;
-    const size_t need = (size_t)g->n_layers * g->max_batch * 2 * g->n_kv_heads * g->max_ctx * g->head_dim * esz;
+    const size_t ctx_pad = ((size_t)g->max_ctx + 31) / 32 * 32;
+    const size_t need = (size_t)g->n_layers * g->max_batch * 2 * g->n_kv_heads * ctx_pad * g->head_dim * esz;
     if (g->kv_cache && g->kv_bytes < need) return "borrowed kv_cache is smaller than the cache layout";
     return nullptr;
 }
@@ -142,6 +143,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     if (!c) return report(WISV_ENOMEM, "host allocation failed");
     c->cfg = *config;
     c->stream = (hipStream_t)config->hip_stream;
+    c->ctx_pad = (config->max_ctx + 31) / 32 * 32;
     c->stream_owned = false;
     c->graph_exec = nullptr;
     c->graph_len_ub = -1;
@@ -277,7 +279,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     }
 
     // ---- KV cache and stream state
-    const size_t kv_elems = (size_t)g.n_layers * g.max_batch * 2 * g.n_kv_heads * g.max_ctx * g.head_dim;
+    const size_t kv_elems = (size_t)g.n_layers * g.max_batch * 2 * g.n_kv_heads * c->ctx_pad * g.head_dim;
     if (g.kv_cache) {
         c->kv = g.kv_cache;
         c->kv_owned = false;
@@ -661,18 +663,29 @@ static int kv_copy(Ctx *c, int32_t stream_id, int32_t layer, void *host_k, void 
     if (len == 0) return WISV_OK;
     HIP_TRY(c, hipSetDevice(g.device_id));
     const size_t row = (size_t)g.head_dim * c->esz;
-    for (int which = 0; which < 2; ++which) {
-        char *dev = (char *)kv_ptr(c, layer, stream_id, which);
-        char *host = (char *)(which ? host_v : host_k);
-        // device pitch: max_ctx rows per head; host pitch: len rows per head
-        if (to_device)
-            HIP_TRY(c, hipMemcpy2DAsync(dev, (size_t)g.max_ctx * row, host, (size_t)len * row, (size_t)len * row,
-                                        g.n_kv_heads, hipMemcpyHostToDevice, c->stream));
-        else
-            HIP_TRY(c, hipMemcpy2DAsync(host, (size_t)len * row, dev, (size_t)g.max_ctx * row, (size_t)len * row,
-                                        g.n_kv_heads, hipMemcpyDeviceToHost, c->stream));
+    // K: device pitch ctx_pad rows per head, host pitch len rows per head
+    char *dev_k = (char *)kv_ptr(c, layer, stream_id, 0);
+    if (to_device)
+        HIP_TRY(c, hipMemcpy2DAsync(dev_k, (size_t)c->ctx_pad * row, host_k, (size_t)len * row, (size_t)len * row,
+                                    g.n_kv_heads, hipMemcpyHostToDevice, c->stream));
+    else
+        HIP_TRY(c, hipMemcpy2DAsync(host_k, (size_t)len * row, dev_k, (size_t)c->ctx_pad * row, (size_t)len * row,
+                                    g.n_kv_heads, hipMemcpyDeviceToHost, c->stream));
+    // V: through a row-major staging buffer on the device, re-blocked by a kernel
+    const size_t v_bytes = (size_t)g.n_kv_heads * len * row;
+    void *stage = nullptr;
+    HIP_TRY(c, hipMalloc(&stage, v_bytes));
+    hipError_t e = hipSuccess;
+    if (to_device) {
+        e = hipMemcpyAsync(stage, host_v, v_bytes, hipMemcpyHostToDevice, c->stream);
+        if (e == hipSuccess) launch_v_reblock(c, stage, kv_ptr(c, layer, stream_id, 1), len, true);
+    } else {
+        launch_v_reblock(c, stage, kv_ptr(c, layer, stream_id, 1), len, false);
+        e = hipMemcpyAsync(host_v, stage, v_bytes, hipMemcpyDeviceToHost, c->stream);
     }
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    (void)hipFree(stage);
+    HIP_TRY(c, e);
     return WISV_OK;
 }
 

@@ -110,7 +110,10 @@ struct Ctx {
     int din_pad;                     // d_draft + d_model + d_csi rounded up to a multiple of 32
     float *rope_cos, *rope_sin;      // [max_ctx][head_dim/2]
 
-    // KV cache [n_layers][max_batch][2][n_kv_heads][max_ctx][head_dim]
+    // KV cache [n_layers][max_batch][2][n_kv_heads] planes of ctx_pad * head_dim elements (ctx_pad = max_ctx rounded
+    // up to 32): K plane [ctx_pad][head_dim]; V plane in blocks of 32 positions, [ctx_pad / 32][head_dim][32], so
+    // that 32 cached values of one feature are contiguous (the k dimension of P.V runs over positions)
+    int ctx_pad;
     void *kv;
     bool kv_owned;
 
@@ -165,6 +168,7 @@ struct Fwd {
 // ---------------------------------------------------------------- kernel launchers (kernels_ref.hip)
 void launch_prep_rows(Ctx *c, const Fwd &f);
 void launch_embed(Ctx *c, const Fwd &f);
+void launch_v_reblock(Ctx *c, void *rows, void *plane, int len, bool to_plane);
 // x += sum of n_partial slices of y (if n_partial > 0); out = RMSNorm(x) * g; optional second float copy
 void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, const ActBuf &out, float *out_f32);
 // Y[rows, n] = A[rows, kd] * W[n, kd]^T (float accumulate, float out)
@@ -205,5 +209,9 @@ struct ProfScope {
 };
 
 void *kv_ptr(const Ctx *c, int layer, int slot, int which);   // which: 0 = K, 1 = V
+// offset of (position, feature) inside one head's V plane
+__host__ __device__ __forceinline__ size_t v_plane_index(int pos, int dim, int hd) {
+    return ((size_t)(pos >> 5) * hd + dim) * 32 + (pos & 31);
+}
 
 }  // namespace wisv

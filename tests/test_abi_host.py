@@ -76,3 +76,22 @@ def test_null_context_is_handled():
     assert lib.wisv_verify_round(None, None, None) == binding.WISV_EINVAL
     assert lib.wisv_last_error(None) == b""
     assert lib.wisv_set_state(None, 0, 0, 0) == binding.WISV_EINVAL
+
+
+def test_kv_fill_follows_the_documented_cache_layout():
+    """K plane position-major, V plane in blocks of 32 positions with element (pos, dim) at
+    ((pos // 32) * head_dim + dim) * 32 + pos % 32 (include/wisv.h, wisv_config.kv_cache)."""
+    import torch
+    m = configs.TINY
+    kv = binding.new_kv_cache(m, 2, 70, "cpu")
+    g, hd = m.n_kv_heads, m.head_dim
+    assert kv.shape[-1] == binding.ctx_pad(70) * hd == 96 * hd
+    gen_ = torch.Generator().manual_seed(1)
+    k, v = torch.randn(g, 45, hd, generator=gen_), torch.randn(g, 45, hd, generator=gen_)
+    binding.kv_fill(kv, m, 1, 1, k, v)
+    for gh in range(g):
+        for pos in (0, 1, 31, 32, 44):
+            for dim in (0, 5, hd - 1):
+                assert kv[1, 1, 1][gh, ((pos // 32) * hd + dim) * 32 + pos % 32] == v[gh, pos, dim]
+                assert kv[1, 1, 0][gh, pos * hd + dim] == k[gh, pos, dim]
+    assert float(kv[0].abs().sum()) == 0.0 and float(kv[1, 0].abs().sum()) == 0.0

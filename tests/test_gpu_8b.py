@@ -53,15 +53,14 @@ def _run(w, target8b, sampled, tol=TOL_BF16):
     t0 = time.time()
     m = w.model
     max_ctx = w.ctx + w.k
-    kv = torch.zeros((m.n_layers, w.batch, 2, m.n_kv_heads, max_ctx, m.head_dim), dtype=torch.bfloat16, device=DEV)
+    kv = binding.new_kv_cache(m, w.batch, max_ctx, DEV)
     ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
     side = OracleSide(w, wh)
     pred_next = []
     for b in range(w.batch):
         for l in range(m.n_layers):
             k, v = gen.synthetic_kv(w, b, l, DEV)
-            kv[l, b, 0, :, :w.ctx] = k
-            kv[l, b, 1, :, :w.ctx] = v
+            binding.kv_fill(kv, m, l, b, k, v)
         pn = gen.synthetic_pred_next(w, b)
         pred_next.append(pn)
         ctx.wisv_set_state(b, w.ctx, pn)
