@@ -38,6 +38,7 @@ struct AttnArgs {
 template <int NQ, int NW>
 __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int MERGE_BYTES = NW * NQ * (2 * 16 * 4 + 8 * 64 * 16);   // the end-of-kernel merge area comes first
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, bj = lane & 15, bg = lane >> 4;
     const int m0 = b * a.K;
@@ -72,13 +73,19 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         WISV_ATTN_LOAD_V(s)
     }
 
-    // ---- queries as MFMA B operands (two bf16 terms): lane (bj, bg) holds Q[rho = 16 nq + bj][32 t + 8 bg ..]
-    u32x4 qhi[NQ][4], qlo[NQ][4];
+    // ---- queries as MFMA B operands (two bf16 terms): lane (bj, bg) holds Q[rho = 16 nq + bj][32 t + 8 bg ..].
+    //      One query tile lives in registers; more would crowd out the accumulators, so they are parked in LDS
+    //      (every wave builds the same operands; wave 0 stores them) and re-read at each use.
+    constexpr bool Q_IN_LDS = NQ > 1;
+    constexpr int QREG = Q_IN_LDS ? 1 : NQ;
+    u32x4 qhi[QREG][4], qlo[QREG][4];
+    u32x4 *qs = reinterpret_cast<u32x4 *>(lds + MERGE_BYTES);   // [NQ][4][2][64]
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         const int rho = nq * 16 + bj;
         const bool valid = rho < R;
         const float *qp = a.q + ((size_t)(m0 + (valid ? rho / a.rep : 0)) * a.H + (size_t)g * a.rep + (valid ? rho % a.rep : 0)) * HD;
+        if (Q_IN_LDS && wave != 0) continue;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             uint32_t h[4] = {0, 0, 0, 0}, l[4] = {0, 0, 0, 0};
@@ -95,10 +102,16 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
                     l[e] = l0 | ((uint32_t)l1 << 16);
                 }
             }
-            qhi[nq][t] = u32x4{h[0], h[1], h[2], h[3]};
-            qlo[nq][t] = u32x4{l[0], l[1], l[2], l[3]};
+            if (Q_IN_LDS) {
+                qs[((nq * 4 + t) * 2 + 0) * 64 + lane] = u32x4{h[0], h[1], h[2], h[3]};
+                qs[((nq * 4 + t) * 2 + 1) * 64 + lane] = u32x4{l[0], l[1], l[2], l[3]};
+            } else {
+                qhi[nq][t] = u32x4{h[0], h[1], h[2], h[3]};
+                qlo[nq][t] = u32x4{l[0], l[1], l[2], l[3]};
+            }
         }
     }
+    if (Q_IN_LDS) __syncthreads();
 
     float m_run[NQ], l_run[NQ];
     floatx4 oacc[NQ][8];
@@ -120,14 +133,18 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
             floatx4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]),
-                                                             *reinterpret_cast<bf16x8 *>(&qhi[nq][t]), sa, 0, 0, 0);
-                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&kb[t]),
-                                                             *reinterpret_cast<bf16x8 *>(&qhi[nq][t]), sb, 0, 0, 0);
-                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]),
-                                                             *reinterpret_cast<bf16x8 *>(&qlo[nq][t]), sa, 0, 0, 0);
-                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&kb[t]),
-                                                             *reinterpret_cast<bf16x8 *>(&qlo[nq][t]), sb, 0, 0, 0);
+                u32x4 qh, ql;
+                if (Q_IN_LDS) {
+                    qh = qs[((nq * 4 + t) * 2 + 0) * 64 + lane];
+                    ql = qs[((nq * 4 + t) * 2 + 1) * 64 + lane];
+                } else {
+                    qh = qhi[nq][t];
+                    ql = qlo[nq][t];
+                }
+                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]), *reinterpret_cast<bf16x8 *>(&qh), sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&kb[t]), *reinterpret_cast<bf16x8 *>(&qh), sb, 0, 0, 0);
+                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&ka[t]), *reinterpret_cast<bf16x8 *>(&ql), sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&kb[t]), *reinterpret_cast<bf16x8 *>(&ql), sb, 0, 0, 0);
             }
             // lane holds keys kbase + e (e = 0..3 from tile A, 4..7 from tile B) of query rho = 16 nq + bj
             const int rho = nq * 16 + bj;
@@ -164,6 +181,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
             }
             phi[nq] = u32x4{h[0], h[1], h[2], h[3]};
             plo[nq] = u32x4{l[0], l[1], l[2], l[3]};
+            __builtin_amdgcn_sched_barrier(0);   // one query tile at a time: their temporaries must not pile up
         }
         // the K registers are free: request the next step's keys
         if (more) { WISV_ATTN_LOAD_K(s + NW) }
@@ -273,7 +291,7 @@ __global__ void k_attn_combine(const float *__restrict__ po, const float *__rest
 }
 
 template <int NQ, int NW> static bool launch_nq(Ctx *c, const AttnArgs &a, dim3 grid) {
-    const size_t lds = (size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16);
+    const size_t lds = (size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16) + (NQ > 1 ? (size_t)NQ * 8 * 1024 : 0);   // merge area + parked queries
     static bool opted_in = false;
     if (lds > 64 * 1024 && !opted_in) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_mfma<NQ, NW>), hipFuncAttributeMaxDynamicSharedMemorySize,
