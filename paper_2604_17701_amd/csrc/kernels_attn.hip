@@ -67,10 +67,13 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         const bf16_t *pv_ = vc + ((size_t)(s_) * HD + bj) * STEP + 8 * bg;                                \
         _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) va[dt] = *reinterpret_cast<const u32x4 *>(pv_ + (size_t)dt * 16 * STEP); \
     }
+    // (no load below is conditional - a branch around a load makes the compiler wait for it on the spot: a wave
+    // without a further step re-reads a step that exists and ignores it)
     int s = s_begin + wave;
-    if (s < s_end) {
-        WISV_ATTN_LOAD_K(s)
-        WISV_ATTN_LOAD_V(s)
+    {
+        const int s0 = min(s, n_steps - 1);
+        WISV_ATTN_LOAD_K(s0)
+        WISV_ATTN_LOAD_V(s0)
     }
 
     // ---- queries as MFMA B operands (two bf16 terms): lane (bj, bg) holds Q[rho = 16 nq + bj][32 t + 8 bg ..].
@@ -86,21 +89,27 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         const bool valid = rho < R;
         const float *qp = a.q + ((size_t)(m0 + (valid ? rho / a.rep : 0)) * a.H + (size_t)g * a.rep + (valid ? rho % a.rep : 0)) * HD;
         if (Q_IN_LDS && wave != 0) continue;
+        // all eight loads first, then the arithmetic; rows past R load row 0 (no branch around the loads) and
+        // become zero
+        float4 xq[4][2];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            uint32_t h[4] = {0, 0, 0, 0}, l[4] = {0, 0, 0, 0};
-            if (valid) {
-                const float4 x0 = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg);
-                const float4 x1 = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg + 4);
-                const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+            xq[t][0] = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg);
+            xq[t][1] = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg + 4);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    bf16_t h0, l0, h1, l1;
-                    split2(xs[2 * e], h0, l0);
-                    split2(xs[2 * e + 1], h1, l1);
-                    h[e] = h0 | ((uint32_t)h1 << 16);
-                    l[e] = l0 | ((uint32_t)l1 << 16);
-                }
+        for (int t = 0; t < 4; ++t) {
+            uint32_t h[4], l[4];
+            const float4 x0 = xq[t][0], x1 = xq[t][1];
+            const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                bf16_t h0, l0, h1, l1;
+                split2(valid ? xs[2 * e] : 0.f, h0, l0);
+                split2(valid ? xs[2 * e + 1] : 0.f, h1, l1);
+                h[e] = h0 | ((uint32_t)h1 << 16);
+                l[e] = l0 | ((uint32_t)l1 << 16);
             }
             if (Q_IN_LDS) {
                 qs[((nq * 4 + t) * 2 + 0) * 64 + lane] = u32x4{h[0], h[1], h[2], h[3]};
@@ -126,7 +135,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
     for (; s < s_end; s += NW) {
         const int kbase = s * STEP + 8 * bg;     // this lane's eight keys: kbase .. kbase + 7
-        const bool more = s + NW < s_end;
+        const int s_next = min(s + NW, n_steps - 1);
         u32x4 phi[NQ], plo[NQ];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
@@ -184,7 +193,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
             __builtin_amdgcn_sched_barrier(0);   // one query tile at a time: their temporaries must not pile up
         }
         // the K registers are free: request the next step's keys
-        if (more) { WISV_ATTN_LOAD_K(s + NW) }
+        WISV_ATTN_LOAD_K(s_next)
         // positions past the end of the sequence may hold anything (0 x NaN would poison the sum): clear them
         if (s * STEP + STEP > n_keys) {
 #pragma unroll
@@ -206,7 +215,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
                                                                       *reinterpret_cast<bf16x8 *>(&plo[nq]), oacc[nq][dt], 0, 0, 0);
             }
         }
-        if (more) { WISV_ATTN_LOAD_V(s + NW) }
+        WISV_ATTN_LOAD_V(s_next)
     }
 #undef WISV_ATTN_LOAD_K
 #undef WISV_ATTN_LOAD_V
