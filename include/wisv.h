@@ -65,6 +65,15 @@ typedef enum { WISV_ACT_SILU = 0, WISV_ACT_RELU = 1 /* eq. mlp_form */ } wisv_ac
 #define WISV_FLAG_NO_COMMIT 2u   /* leave kv_len / pred_next of the streams unchanged */
 #define WISV_FLAG_DEVICE_IO 4u   /* all round_in / round_out pointers are device pointers; enqueue only */
 #define WISV_FLAG_KEEP_LOGITS 8u /* also materialise fp32 logits for wisv_debug_copy (debug, slow) */
+/* The selective-hidden protocol in two calls (Alg. 1: Verify, Localize, RequestHidden(S), then the head on the
+ * uploaded rows; Sec. III-B).  VERIFY_ONLY runs the target forward and the localisation: target_argmax and
+ * mismatch_mask (the request message) are final, nothing is committed, and accepted_len / correction_token are
+ * those of plain greedy verification (no hidden state has been uploaded yet).  DECIDE_ONLY, given next for the
+ * same streams, k and draft tokens, skips the forward: it runs the decision head on the rows uploaded now, the
+ * first-reject scan and the commit.  Both together, or DECIDE_ONLY without a matching VERIFY_ONLY before it, are
+ * errors (WISV_EINVAL / WISV_ESTATE). */
+#define WISV_FLAG_VERIFY_ONLY 16u
+#define WISV_FLAG_DECIDE_ONLY 32u
 
 /* wisv_round_out.status bits */
 #define WISV_STATUS_MISSING_HIDDEN 1u /* a gated position had no h^D row: it was rejected */

@@ -21,6 +21,7 @@ WISV_F32, WISV_BF16 = 0, 1
 WISV_PROTO_FH, WISV_PROTO_SH = 0, 1
 WISV_ACT_SILU, WISV_ACT_RELU = 0, 1
 WISV_FLAG_GATE_ALL, WISV_FLAG_NO_COMMIT, WISV_FLAG_DEVICE_IO, WISV_FLAG_KEEP_LOGITS = 1, 2, 4, 8
+WISV_FLAG_VERIFY_ONLY, WISV_FLAG_DECIDE_ONLY = 16, 32
 WISV_STATUS_MISSING_HIDDEN = 1
 WISV_DBG_HIDDEN, WISV_DBG_LOGITS = 0, 1
 WISV_MAX_K = 16

@@ -443,8 +443,13 @@ static int check_round(Ctx *c, const wisv_round_in *in, const wisv_round_out *ou
         return fail(c, WISV_EINVAL, "hd_row is NULL (identity map) but n_hd != batch*k");
     if (!out->accepted_len || !out->correction_token || !out->p_accept)
         return fail(c, WISV_EINVAL, "a required round_out pointer is NULL");
-    if (in->flags & ~(WISV_FLAG_GATE_ALL | WISV_FLAG_NO_COMMIT | WISV_FLAG_DEVICE_IO | WISV_FLAG_KEEP_LOGITS))
+    if (in->flags & ~(WISV_FLAG_GATE_ALL | WISV_FLAG_NO_COMMIT | WISV_FLAG_DEVICE_IO | WISV_FLAG_KEEP_LOGITS |
+                      WISV_FLAG_VERIFY_ONLY | WISV_FLAG_DECIDE_ONLY))
         return fail(c, WISV_EINVAL, "unknown flag bits 0x%x", in->flags);
+    if ((in->flags & WISV_FLAG_VERIFY_ONLY) && (in->flags & WISV_FLAG_DECIDE_ONLY))
+        return fail(c, WISV_EINVAL, "WISV_FLAG_VERIFY_ONLY and WISV_FLAG_DECIDE_ONLY exclude each other");
+    if ((in->flags & (WISV_FLAG_VERIFY_ONLY | WISV_FLAG_DECIDE_ONLY)) && (in->flags & WISV_FLAG_DEVICE_IO))
+        return fail(c, WISV_EUNSUPPORTED, "the two-call protocol takes host buffers (it checks that both calls name the same round)");
     return WISV_OK;
 }
 
@@ -455,7 +460,8 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
     if (rc) return rc;
     const wisv_config &g = c->cfg;
     const int B = in->batch, K = in->k, R = B * K;
-    const bool dev_io = in->flags & WISV_FLAG_DEVICE_IO, commit = !(in->flags & WISV_FLAG_NO_COMMIT);
+    const bool verify_only = in->flags & WISV_FLAG_VERIFY_ONLY, decide_only = in->flags & WISV_FLAG_DECIDE_ONLY;
+    const bool dev_io = in->flags & WISV_FLAG_DEVICE_IO, commit = !(in->flags & WISV_FLAG_NO_COMMIT) && !verify_only;
 
     int len_ub = 0;
     if (!dev_io) {
@@ -486,6 +492,15 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
         if (len_ub > g.max_ctx)
             return fail(c, WISV_ESTATE, "a stream may exceed max_ctx; resynchronise with wisv_get_state");
     }
+
+    // the two-call protocol: the second call must name the round the first one ran
+    if (decide_only) {
+        bool same = c->pending_valid && c->pending_batch == B && c->pending_k == K;
+        for (int b = 0; same && b < B; ++b) same = c->pending_ids[b] == in->stream_ids[b];
+        for (int m = 0; same && m < R; ++m) same = c->pending_tokens[m] == in->draft_tokens[m];
+        if (!same) return fail(c, WISV_ESTATE, "WISV_FLAG_DECIDE_ONLY without a WISV_FLAG_VERIFY_ONLY call for the same round before it");
+    }
+    c->pending_valid = false;   // any round overwrites what a VERIFY_ONLY call left behind
 
     HIP_TRY(c, hipSetDevice(g.device_id));
     wisv_round_in din = *in;
@@ -542,7 +557,14 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
         const bool capture = same_call;   // the first call of a kind always runs eagerly (one-time kernel attribute set-up)
         if (capture) HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
         { ProfScope empty(c, KC_EMPTY); }   // an event pair with nothing in between: what the bracketing itself costs
-        enqueue_forward(c, f);
+        if (!decide_only) enqueue_forward(c, f);   // else: h^T, the greedy tokens and the appended K/V are still there
+        if (verify_only) {
+            // localisation only: no hidden state counts as uploaded, nothing is committed
+            din.n_hd = 0;
+            din.hd_row = c->d_hd_row;
+            HIP_TRY(c, hipMemsetAsync(c->d_hd_row, 0xff, (size_t)R * 4, c->stream));   // every row: -1, not uploaded
+            din.flags |= WISV_FLAG_NO_COMMIT;
+        }
         launch_head_decide(c, f, din, dout);
         if (capture) {
             hipGraph_t graph = nullptr;
@@ -578,6 +600,13 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
         for (int b = 0; b < B; ++b) {
             out->accepted_len[b] = alen[b];
             if (commit) c->h_len_ub[in->stream_ids[b]] += alen[b];
+        }
+        if (verify_only) {
+            c->pending_valid = true;
+            c->pending_batch = B;
+            c->pending_k = K;
+            c->pending_ids.assign(in->stream_ids, in->stream_ids + B);
+            c->pending_tokens.assign(in->draft_tokens, in->draft_tokens + R);
         }
     } else if (commit) {
         for (int s = 0; s < g.max_batch; ++s) c->h_len_ub[s] = std::min(c->h_len_ub[s] + K, g.max_ctx);

@@ -147,6 +147,10 @@ struct Ctx {
     double prof_ms[KC_COUNT];
     long prof_n[KC_COUNT];
     int last_rows;
+    // the round a WISV_FLAG_VERIFY_ONLY call left for its WISV_FLAG_DECIDE_ONLY call
+    bool pending_valid;
+    int pending_batch, pending_k;
+    std::vector<int32_t> pending_ids, pending_tokens;
 
     std::string err;
     std::vector<void *> owned;    // device allocations to free

@@ -139,6 +139,50 @@ def test_config0_threshold_extremes_and_chain_draft():
     ctx.wisv_destroy()
 
 
+def test_selective_hidden_protocol_in_two_calls():
+    """Alg. 1 as the wire protocol runs it: Verify + Localize (the mask is the request message), then the
+    head on exactly the requested rows.  The second call must give what the one-shot round gives, which
+    the oracle checks in the parity tests; the first call's accepted length is plain greedy verification."""
+    dev = torch.device("cuda:0")
+    w = replace(W0, protos=(PROTO_SH,))
+    wd = gen.make_weights(w.model, w.seed, dev)
+    side = OracleSide(w, to_host_weights(wd))
+    ctx = _ctx(w, wd)
+    ctx.wisv_prefill(0, gen.context_tokens(w, 0))
+    side.prefill(0)
+    ins = side.stream_inputs(0)
+    hd_all, csi, k = gen.draft_hidden(w, 0), gen.csi_features(w), w.k
+    tau, nc = 0.5, binding.WISV_FLAG_NO_COMMIT
+    want_s = list(ins.mismatch)
+    # one-shot reference (device already knows S) and the oracle
+    rows = np.full(k, -1, np.int32)
+    rows[want_s] = np.arange(len(want_s))
+    one = ctx.wisv_verify_round([0], ins.draft, [PROTO_SH], hd_all[want_s] if want_s else None, rows, csi, [tau], k, nc)
+    o = side.round(0, ins, PROTO_SH, hd_all[want_s], rows, csi[0], tau, want_logits=False)
+    compare_stream(one, 0, o, k, tau, TOL_F32, {}, None)
+    state0 = ctx.wisv_get_state(0)
+    # call 1: forward + localisation, nothing uploaded, nothing committed
+    first = ctx.wisv_verify_round([0], ins.draft, [PROTO_SH], None, np.full(k, -1), csi, [tau], k, binding.WISV_FLAG_VERIFY_ONLY)
+    got_s = [j for j in range(k) if (int(first["mismatch_mask"][0]) >> j) & 1]
+    assert got_s == want_s
+    np.testing.assert_array_equal(first["target_argmax"], one["target_argmax"])
+    assert first["accepted_len"][0] == (want_s[0] if want_s else k)          # greedy verification
+    assert ctx.wisv_get_state(0) == state0
+    # call 2: the requested rows arrive; no forward; commit
+    second = ctx.wisv_verify_round([0], ins.draft, [PROTO_SH], hd_all[got_s] if got_s else None, rows, csi, [tau], k,
+                                   binding.WISV_FLAG_DECIDE_ONLY)
+    for key in ("accepted_len", "correction_token", "p_accept", "target_argmax", "mismatch_mask", "status"):
+        assert np.array_equal(second[key], one[key]), key
+    assert ctx.wisv_get_state(0) == (state0[0] + int(one["accepted_len"][0]), int(one["correction_token"][0]))
+    # the pending round is consumed; a decide call for another round is refused
+    with pytest.raises(binding.WisvError):
+        ctx.wisv_verify_round([0], ins.draft, [PROTO_SH], None, np.full(k, -1), csi, [tau], k, binding.WISV_FLAG_DECIDE_ONLY)
+    with pytest.raises(binding.WisvError):
+        ctx.wisv_verify_round([0], ins.draft, [PROTO_SH], None, np.full(k, -1), csi, [tau], k,
+                              binding.WISV_FLAG_DECIDE_ONLY | binding.WISV_FLAG_VERIFY_ONLY)
+    ctx.wisv_destroy()
+
+
 def test_commit_advances_the_stream_state():
     dev = torch.device("cuda:0")
     w = W0
