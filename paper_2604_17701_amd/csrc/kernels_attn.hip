@@ -32,10 +32,17 @@ struct AttnArgs {
     const int32_t *row_slot, *row_pos;
     float *po, *pm, *pl;      // partials [split][rows][H][128], [split][rows][H]  (n_splits > 1)
     ActBuf o;                 // attention output [rows][H][128]                    (n_splits == 1)
+    // FUSE: the kernel sums the k-split slices of the QKV product itself, rotates q and k, appends k and v
+    const float *qkv;         // [n_partial][partial_stride] slices of [rows][H*128 + 2 G*128]
+    int n_partial;
+    size_t partial_stride;
+    const float *cs, *sn;     // rotary tables [max_ctx][64]
+    bf16_t *kv_write;         // == kv_layer
 };
 
-// NQ: 16-row query tiles; NW: waves per workgroup
-template <int NQ, int NW>
+// NQ: 16-row query tiles; NW: waves per workgroup; FUSE: RoPE and the cache append happen here (single k-split only:
+// the one workgroup of a (stream, KV head) writes the new rows before any of its waves reads them)
+template <int NQ, int NW, bool FUSE>
 __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int MERGE_BYTES = NW * NQ * (2 * 16 * 4 + 8 * 64 * 16);   // the end-of-kernel merge area comes first
@@ -67,60 +74,137 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         const bf16_t *pv_ = vc + ((size_t)(s_) * HD + bj) * STEP + 8 * bg;                                \
         _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) va[dt] = *reinterpret_cast<const u32x4 *>(pv_ + (size_t)dt * 16 * STEP); \
     }
-    // (no load below is conditional - a branch around a load makes the compiler wait for it on the spot: a wave
-    // without a further step re-reads a step that exists and ignores it)
+    constexpr bool Q_IN_LDS = NQ > 1 || FUSE;
+    constexpr int QREG = NQ > 1 ? 1 : NQ;
+    u32x4 qhi[QREG][4], qlo[QREG][4];
+    u32x4 *qs = reinterpret_cast<u32x4 *>(lds + MERGE_BYTES);   // [NQ][4][2][64] query operands
     int s = s_begin + wave;
-    {
+    if (FUSE) {
+        // this wave's first step is requested now; if it holds appended rows it is requested again below
         const int s0 = min(s, n_steps - 1);
         WISV_ATTN_LOAD_K(s0)
         WISV_ATTN_LOAD_V(s0)
+    }
+    if (FUSE) {
+        // ---- RoPE + append.  Work item = (row, pair of features i, i + 64): q rows rho < R of this KV head's query
+        //      heads go, rotated and split into two bf16 terms, straight into the operand layout in LDS; the K new
+        //      rows of k (rotated) and v go to the cache.  Slices are added in slice order.
+        const int d_q = a.H * HD, d_kv = a.G * HD, d_all = d_q + 2 * d_kv;
+        bf16_t *kw = a.kv_write + (size_t)slot * a.slot_stride + (size_t)g * a.ctx_pad * HD;
+        bf16_t *vw = kw + (size_t)a.G * a.ctx_pad * HD;
+        bf16_t *q16 = reinterpret_cast<bf16_t *>(qs);
+        for (int it = tid; it < (16 * NQ + 2 * a.K) * 64; it += 64 * NW) {
+            const int row = it >> 6, i = it & 63;
+            int j, col;                      // token of the block, first column of the head in a qkv row
+            if (row < 16 * NQ) {
+                const int rho = min(row, R - 1);
+                j = rho / a.rep;
+                col = (g * a.rep + rho % a.rep) * HD;
+            } else if (row < 16 * NQ + a.K) {
+                j = row - 16 * NQ;
+                col = d_q + g * HD;
+            } else {
+                j = row - 16 * NQ - a.K;
+                col = d_q + d_kv + g * HD;
+            }
+            const float *src = a.qkv + (size_t)(m0 + j) * d_all + col;
+            // every slice is requested before the first is used (slices past the last re-read it and count as 0)
+            float xs[MAX_SPLITS], ys[MAX_SPLITS];
+#pragma unroll
+            for (int p = 0; p < MAX_SPLITS; ++p) {
+                const size_t off = (size_t)min(p, a.n_partial - 1) * a.partial_stride;
+                xs[p] = src[off + i];
+                ys[p] = src[off + i + 64];
+            }
+            float x = xs[0], y = ys[0];
+#pragma unroll
+            for (int p = 1; p < MAX_SPLITS; ++p) {
+                x += p < a.n_partial ? xs[p] : 0.f;
+                y += p < a.n_partial ? ys[p] : 0.f;
+            }
+            const int pos = min(L + j, a.max_ctx - 1);
+            const float co = a.cs[(size_t)pos * 64 + i], si = a.sn[(size_t)pos * 64 + i];
+            if (row < 16 * NQ) {
+                const float r0 = row < R ? x * co - y * si : 0.f, r1 = row < R ? y * co + x * si : 0.f;
+                // element (rho, dim) of operand (nq, t = dim / 32, plane): lane 16 ((dim % 32) / 8) + rho % 16, slot dim % 8
+                const int nq = row >> 4, bjq = row & 15;
+                bf16_t h0, l0, h1, l1;
+                split2(r0, h0, l0);
+                split2(r1, h1, l1);
+                const int e = i & 7, ln = 16 * ((i & 31) >> 3) + bjq, t0 = i >> 5;
+                q16[((((nq * 4 + t0) * 2 + 0) * 64 + ln) << 3) + e] = h0;
+                q16[((((nq * 4 + t0) * 2 + 1) * 64 + ln) << 3) + e] = l0;
+                q16[((((nq * 4 + t0 + 2) * 2 + 0) * 64 + ln) << 3) + e] = h1;
+                q16[((((nq * 4 + t0 + 2) * 2 + 1) * 64 + ln) << 3) + e] = l1;
+            } else if (row < 16 * NQ + a.K) {
+                kw[(size_t)pos * HD + i] = f32_to_bf16(x * co - y * si);
+                kw[(size_t)pos * HD + i + 64] = f32_to_bf16(y * co + x * si);
+            } else {
+                vw[v_plane_index(pos, i, HD)] = f32_to_bf16(x);
+                vw[v_plane_index(pos, i + 64, HD)] = f32_to_bf16(y);
+            }
+        }
+        __syncthreads();   // the appended rows and the query operands are visible to the whole workgroup
+    }
+    // (no load below is conditional - a branch around a load makes the compiler wait for it on the spot: a wave
+    // without a further step re-reads a step that exists and ignores it)
+    {
+        const int s0 = min(s, n_steps - 1);
+        if (!FUSE || (s0 + 1) * STEP > L) {
+            WISV_ATTN_LOAD_K(s0)
+            WISV_ATTN_LOAD_V(s0)
+        }
     }
 
     // ---- queries as MFMA B operands (two bf16 terms): lane (bj, bg) holds Q[rho = 16 nq + bj][32 t + 8 bg ..].
     //      One query tile lives in registers; more would crowd out the accumulators, so they are parked in LDS
     //      (every wave builds the same operands; wave 0 stores them) and re-read at each use.
-    constexpr bool Q_IN_LDS = NQ > 1;
-    constexpr int QREG = Q_IN_LDS ? 1 : NQ;
-    u32x4 qhi[QREG][4], qlo[QREG][4];
-    u32x4 *qs = reinterpret_cast<u32x4 *>(lds + MERGE_BYTES);   // [NQ][4][2][64]
+    if (!FUSE) {
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const int rho = nq * 16 + bj;
-        const bool valid = rho < R;
-        const float *qp = a.q + ((size_t)(m0 + (valid ? rho / a.rep : 0)) * a.H + (size_t)g * a.rep + (valid ? rho % a.rep : 0)) * HD;
-        if (Q_IN_LDS && wave != 0) continue;
-        // all eight loads first, then the arithmetic; rows past R load row 0 (no branch around the loads) and
-        // become zero
-        float4 xq[4][2];
+        for (int nq = 0; nq < NQ; ++nq) {
+            const int rho = nq * 16 + bj;
+            const bool valid = rho < R;
+            const float *qp = a.q + ((size_t)(m0 + (valid ? rho / a.rep : 0)) * a.H + (size_t)g * a.rep + (valid ? rho % a.rep : 0)) * HD;
+            if (NQ > 1 && wave != 0) continue;
+            // all eight loads first, then the arithmetic; rows past R load row 0 (no branch around the loads) and
+            // become zero
+            float4 xq[4][2];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            xq[t][0] = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg);
-            xq[t][1] = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg + 4);
+            for (int t = 0; t < 4; ++t) {
+                xq[t][0] = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg);
+                xq[t][1] = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg + 4);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                uint32_t h[4], l[4];
+                const float4 x0 = xq[t][0], x1 = xq[t][1];
+                const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    bf16_t h0, l0, h1, l1;
+                    split2(valid ? xs[2 * e] : 0.f, h0, l0);
+                    split2(valid ? xs[2 * e + 1] : 0.f, h1, l1);
+                    h[e] = h0 | ((uint32_t)h1 << 16);
+                    l[e] = l0 | ((uint32_t)l1 << 16);
+                }
+                if (NQ > 1) {
+                    qs[((nq * 4 + t) * 2 + 0) * 64 + lane] = u32x4{h[0], h[1], h[2], h[3]};
+                    qs[((nq * 4 + t) * 2 + 1) * 64 + lane] = u32x4{l[0], l[1], l[2], l[3]};
+                } else {
+                    qhi[0][t] = u32x4{h[0], h[1], h[2], h[3]};
+                    qlo[0][t] = u32x4{l[0], l[1], l[2], l[3]};
+                }
+            }
         }
-        __builtin_amdgcn_sched_barrier(0);
+        if (NQ > 1) __syncthreads();
+    } else if (NQ == 1) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            uint32_t h[4], l[4];
-            const float4 x0 = xq[t][0], x1 = xq[t][1];
-            const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                bf16_t h0, l0, h1, l1;
-                split2(valid ? xs[2 * e] : 0.f, h0, l0);
-                split2(valid ? xs[2 * e + 1] : 0.f, h1, l1);
-                h[e] = h0 | ((uint32_t)h1 << 16);
-                l[e] = l0 | ((uint32_t)l1 << 16);
-            }
-            if (Q_IN_LDS) {
-                qs[((nq * 4 + t) * 2 + 0) * 64 + lane] = u32x4{h[0], h[1], h[2], h[3]};
-                qs[((nq * 4 + t) * 2 + 1) * 64 + lane] = u32x4{l[0], l[1], l[2], l[3]};
-            } else {
-                qhi[nq][t] = u32x4{h[0], h[1], h[2], h[3]};
-                qlo[nq][t] = u32x4{l[0], l[1], l[2], l[3]};
-            }
+            qhi[0][t] = qs[(t * 2 + 0) * 64 + lane];
+            qlo[0][t] = qs[(t * 2 + 1) * 64 + lane];
         }
     }
-    if (Q_IN_LDS) __syncthreads();
 
     float m_run[NQ], l_run[NQ];
     floatx4 oacc[NQ][8];
@@ -143,7 +227,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 u32x4 qh, ql;
-                if (Q_IN_LDS) {
+                if (NQ > 1) {
                     qh = qs[((nq * 4 + t) * 2 + 0) * 64 + lane];
                     ql = qs[((nq * 4 + t) * 2 + 1) * 64 + lane];
                 } else {
@@ -299,46 +383,63 @@ __global__ void k_attn_combine(const float *__restrict__ po, const float *__rest
     act_store(o, ((size_t)m * H + h) * HD + d, num / den);
 }
 
-template <int NQ, int NW> static bool launch_nq(Ctx *c, const AttnArgs &a, dim3 grid) {
-    const size_t lds = (size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16) + (NQ > 1 ? (size_t)NQ * 8 * 1024 : 0);   // merge area + parked queries
+template <int NQ, int NW, bool FUSE> static bool launch_nq(Ctx *c, const AttnArgs &a, dim3 grid) {
+    // merge area + parked query operands
+    const size_t lds = (size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16) + (NQ > 1 || FUSE ? (size_t)NQ * 8 * 1024 : 0);
     static bool opted_in = false;
     if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_mfma<NQ, NW>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                160 * 1024) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_mfma<NQ, NW, FUSE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return false;
         opted_in = true;
     }
-    hipLaunchKernelGGL((k_attn_mfma<NQ, NW>), grid, dim3(64 * NW), lds, c->stream, a);
+    hipLaunchKernelGGL((k_attn_mfma<NQ, NW, FUSE>), grid, dim3(64 * NW), lds, c->stream, a);
     return true;
 }
 
-bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer) {
+// One workgroup per (stream, KV head) when that fills the chip or the context is short (then the workgroup
+// writes the output itself, and can do RoPE and the cache append on the way in); otherwise k-splits of at
+// least four 32-key steps per wave.  0: the shape is not served.
+static int attn_splits(const Ctx *c, const Fwd &f) {
     const wisv_config &g = c->cfg;
     const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
-    if (!c->bf16 || g.head_dim != HD || R > 64 || f.rows != f.batch * f.k) return false;
+    if (!c->bf16 || g.head_dim != HD || R > 64 || f.rows != f.batch * f.k) return 0;
+    const int nw = R <= 32 ? 8 : 4;
+    const int n_steps = (f.max_len_ub + STEP - 1) / STEP, wgs = f.batch * g.n_kv_heads;
+    const int want = wgs >= 256 ? 1 : std::min((512 + wgs - 1) / wgs, (n_steps + 4 * nw - 1) / (4 * nw));
+    return std::max(1, std::min(want, c->att_max_splits));
+}
+
+bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f) { return attn_splits(c, f) == 1; }
+
+// n_partial > 0: the k-split slices of the QKV product are in c->qkv and the kernel does RoPE and the append
+// itself (only when attn_mfma_fuses_rope); n_partial == 0: launch_rope_append has run
+bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial) {
+    const wisv_config &g = c->cfg;
+    const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
     AttnArgs a;
+    a.n_splits = attn_splits(c, f);
+    if (!a.n_splits || (n_partial > 0 && a.n_splits != 1)) return false;
     a.q = c->q;
     a.kv_layer = (const bf16_t *)kv_ptr(c, layer, 0, 0);
+    a.kv_write = (bf16_t *)kv_ptr(c, layer, 0, 0);
     a.slot_stride = (size_t)2 * g.n_kv_heads * c->ctx_pad * g.head_dim;
     a.H = g.n_heads; a.G = g.n_kv_heads; a.rep = rep; a.K = f.k; a.max_ctx = g.max_ctx; a.ctx_pad = c->ctx_pad; a.rows = f.rows;
     a.row_slot = c->row_slot; a.row_pos = c->row_pos;
     a.po = c->att_o; a.pm = c->att_m; a.pl = c->att_l;
     a.o = c->o;
-    // One workgroup per (stream, KV head) when that fills the chip or the context is short (then the workgroup
-    // writes the output itself); otherwise k-splits of at least four 32-key steps per wave
-    const int nw = R <= 32 ? 8 : 4;
-    const int n_steps = (f.max_len_ub + STEP - 1) / STEP, wgs = f.batch * g.n_kv_heads;
-    int want = wgs >= 256 ? 1 : std::min((512 + wgs - 1) / wgs, (n_steps + 4 * nw - 1) / (4 * nw));
-    a.n_splits = std::max(1, std::min(want, c->att_max_splits));
+    a.qkv = c->qkv; a.n_partial = n_partial; a.partial_stride = (size_t)c->rows_max * c->d_qkv;
+    a.cs = c->rope_cos; a.sn = c->rope_sin;
     dim3 grid(a.n_splits, g.n_kv_heads, f.batch);
     {
         ProfScope ps(c, KC_ATTN);
         bool ok;
+        const bool fuse = n_partial > 0;
         switch ((R + 15) / 16) {
-            case 1: ok = launch_nq<1, 8>(c, a, grid); break;
-            case 2: ok = launch_nq<2, 8>(c, a, grid); break;
-            case 3: ok = launch_nq<3, 4>(c, a, grid); break;
-            default: ok = launch_nq<4, 4>(c, a, grid); break;
+            case 1: ok = fuse ? launch_nq<1, 8, true>(c, a, grid) : launch_nq<1, 8, false>(c, a, grid); break;
+            case 2: ok = fuse ? launch_nq<2, 8, true>(c, a, grid) : launch_nq<2, 8, false>(c, a, grid); break;
+            case 3: ok = fuse ? launch_nq<3, 4, true>(c, a, grid) : launch_nq<3, 4, false>(c, a, grid); break;
+            default: ok = fuse ? launch_nq<4, 4, true>(c, a, grid) : launch_nq<4, 4, false>(c, a, grid); break;
         }
         if (!ok) return false;
     }

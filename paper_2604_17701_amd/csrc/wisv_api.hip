@@ -392,12 +392,15 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             }
         };
         int ny = 0;
+        const bool fuse_rope = attn_mfma_fuses_rope(c, f);
         for (int l = 0; l < g.n_layers; ++l) {
             const LayerW &L = c->layers[l];
             launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
             const int nq = product(L.wqkv_t, L.wqkv, c->a, c->qkv, qs, c->d_qkv, d);
-            launch_rope_append(c, f, l, nq);
-            if (!launch_attn_mfma(c, f, l)) launch_attn_ref(c, f, l);
+            if (!(fuse_rope && launch_attn_mfma(c, f, l, nq))) {
+                launch_rope_append(c, f, l, nq);
+                if (!launch_attn_mfma(c, f, l, 0)) launch_attn_ref(c, f, l);
+            }
             ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
             launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
             gate_up(L);

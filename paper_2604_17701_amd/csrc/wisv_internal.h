@@ -198,7 +198,10 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
 // ---------------------------------------------------------------- split-KV MFMA attention (kernels_attn.hip)
 // true if the shape is served (bf16 cache, head_dim 128, at most 64 query rows per KV head); then c->o holds
 // the attention output of every row
-bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer);
+bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial);
+// true if launch_attn_mfma(.., n_partial > 0) will do RoPE and the cache append itself from the k-split slices of
+// the QKV product (then launch_rope_append must not run)
+bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f);
 
 // records the event pair of one launch when profiling is on
 struct ProfScope {
