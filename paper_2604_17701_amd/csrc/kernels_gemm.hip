@@ -509,17 +509,26 @@ __global__ __launch_bounds__(512) void k_gemm_mm(GemmArgs g) {
 }
 
 // final argmax over the per-group candidates of every row
-__global__ void k_argmax_cand(const float *__restrict__ val, const int32_t *__restrict__ idxs, int n_cand, int stride,
-                              int32_t *amax) {
-    __shared__ float bv[4];
-    __shared__ int bi[4];
+__global__ __launch_bounds__(1024) void k_argmax_cand(const float *__restrict__ val, const int32_t *__restrict__ idxs, int n_cand,
+                                                     int stride, int32_t *amax) {
+    __shared__ float bv[16];
+    __shared__ int bi[16];
     const int m = blockIdx.x, tid = threadIdx.x;
     float best = -INFINITY;
     int idx = 0x7fffffff;
-    for (int i = tid; i < n_cand; i += 256) {
-        const float v = val[(size_t)m * stride + i];
-        const int n = idxs[(size_t)m * stride + i];
-        if (v > best || (v == best && n < idx)) { best = v; idx = n; }
+    // four candidates per pass, all loads first (slots past the end re-read the last one: same value, same index)
+    for (int i0 = tid; i0 < n_cand; i0 += 4096) {
+        float v[4];
+        int n[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = min(i0 + 1024 * u, n_cand - 1);
+            v[u] = val[(size_t)m * stride + i];
+            n[u] = idxs[(size_t)m * stride + i];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (v[u] > best || (v[u] == best && n[u] < idx)) { best = v[u]; idx = n[u]; }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -530,7 +539,7 @@ __global__ void k_argmax_cand(const float *__restrict__ val, const int32_t *__re
     if ((tid & 63) == 0) { bv[tid >> 6] = best; bi[tid >> 6] = idx; }
     __syncthreads();
     if (tid == 0) {
-        for (int w = 1; w < 4; ++w)
+        for (int w = 1; w < 16; ++w)
             if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
         amax[m] = idx == 0x7fffffff ? 0 : idx;
     }
@@ -676,7 +685,7 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     }
     {
         ProfScope ps(c, KC_ARGMAX);
-        hipLaunchKernelGGL(k_argmax_cand, dim3(rows), dim3(256), 0, c->stream, c->cand_val, c->cand_idx, slots, g.n_cand, c->amax);
+        hipLaunchKernelGGL(k_argmax_cand, dim3(rows), dim3(1024), 0, c->stream, c->cand_val, c->cand_idx, slots, g.n_cand, c->amax);
     }
     return true;
 }

@@ -89,24 +89,30 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restr
     const int m = blockIdx.x;
     float *xr = x + (size_t)m * d;
     float ss = 0.f;
-    // 1024 threads, four consecutive elements each per pass; the slices are loaded independently and
-    // added in slice order
+    // 1024 threads, four consecutive elements each per pass.  Every slice is requested before the first is used
+    // (no load sits behind a branch: slices past the last re-read it and count as zero) and added in slice order.
+    // The first pass's elements stay in registers for the second phase.
+    float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i = threadIdx.x * 4; i < d; i += 4096) {
         float4 v = *reinterpret_cast<const float4 *>(xr + i);
         float4 part[MAX_SPLITS];
+        const int np = max(n_partial, 1);
 #pragma unroll
         for (int p = 0; p < MAX_SPLITS; ++p)
-            if (p < n_partial) part[p] = *reinterpret_cast<const float4 *>(y + p * partial_stride + (size_t)m * d + i);
+            part[p] = *reinterpret_cast<const float4 *>(y + (size_t)min(p, np - 1) * partial_stride + (size_t)m * d + i);
 #pragma unroll
-        for (int p = 0; p < MAX_SPLITS; ++p)
-            if (p < n_partial) { v.x += part[p].x; v.y += part[p].y; v.z += part[p].z; v.w += part[p].w; }
+        for (int p = 0; p < MAX_SPLITS; ++p) {
+            const bool on = p < n_partial;   // a select, not a product: the unused re-read may hold anything
+            v.x += on ? part[p].x : 0.f; v.y += on ? part[p].y : 0.f; v.z += on ? part[p].z : 0.f; v.w += on ? part[p].w : 0.f;
+        }
         if (n_partial) *reinterpret_cast<float4 *>(xr + i) = v;
+        if (i < 4096) v0 = v;
         ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
     ss = block_sum<1024>(ss, red);
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     for (int i = threadIdx.x * 4; i < d; i += 4096) {
-        const float4 v = *reinterpret_cast<const float4 *>(xr + i);
+        const float4 v = i < 4096 ? v0 : *reinterpret_cast<const float4 *>(xr + i);
         float4 r;
         r.x = v.x * inv * Elem<WT>::load(g + i);
         r.y = v.y * inv * Elem<WT>::load(g + i + 1);
