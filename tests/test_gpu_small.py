@@ -205,6 +205,50 @@ def test_commit_advances_the_stream_state():
     ctx.wisv_destroy()
 
 
+def test_steady_state_rounds_commit_and_roll_back_like_the_oracle():
+    """Six committed rounds in a row (Sec. IV-B state recursion L' = L + A): every round forwards the not yet
+    cached correction token of the round before as its first "draft" (it matches pred_next by construction)
+    followed by K - 1 tokens of a synthetic drafter that follows the target's greedy chain half of the time.
+    Rejected rows are dead and must be overwritten; lengths, correction tokens, masks and probabilities of
+    every round, the accepted length statistics and the final cache must equal the oracle's."""
+    dev = torch.device("cuda:0")
+    w = W0
+    k, rounds, tau = w.k, 6, 0.5
+    wd = gen.make_weights(w.model, w.seed, dev)
+    side = OracleSide(w, to_host_weights(wd))
+    ctx = _ctx(w, wd, extra_ctx=rounds * k)
+    ctx.wisv_prefill(0, gen.context_tokens(w, 0))
+    side.prefill(0)
+    orc, csi = side.orc, gen.csi_features(w)
+    big = orc.new_cache(w.ctx + k + rounds * k)
+    big[:, :, :, :w.ctx] = side.cache[0][:, :, :, :w.ctx]
+    L, pn = w.ctx, side.pred_next[0]
+    rng = np.random.default_rng(11)
+    accepted = []
+    for r in range(rounds):
+        # the drafter: first the pending token, then the greedy chain or a random token
+        draft = [int(pn)]
+        for j in range(1, k):
+            nxt = int(orc.forward_block(big.copy(), L, draft)["argmax"][-1])
+            draft.append(nxt if rng.random() < 0.5 else int(rng.integers(0, w.model.vocab)))
+        hd = gen.normal(w.seed + r, "steady_hd", (k, w.model.d_draft), 1.0, torch.float32, "cpu")
+        o = orc.verify_round(big, L, pn, draft, PROTO_FH, hd.numpy(), np.arange(k), csi[0], tau)
+        g = ctx.wisv_verify_round([0], draft, [PROTO_FH], hd, None, csi, [tau], k, 0)
+        assert not (int(g["mismatch_mask"][0]) & 1), "the pending token is the target's own"
+        compare_stream(g, 0, o, k, tau, TOL_F32, {}, None)
+        a, y = int(g["accepted_len"][0]), int(g["correction_token"][0])
+        assert a >= 1 and (a, y) == (o["accepted_len"], o["correction_token"])
+        L, pn = L + a, y
+        assert ctx.wisv_get_state(0) == (L, pn)
+        accepted.append(a)
+    assert 1.0 <= sum(accepted) / rounds <= k                     # average accepted length per round
+    for l in range(w.model.n_layers):
+        kk, vv = ctx.wisv_kv_export(0, l, L)
+        np.testing.assert_allclose(kk.numpy(), big[l, 0][:, :L], atol=2e-5)
+        np.testing.assert_allclose(vv.numpy(), big[l, 1][:, :L], atol=2e-5)
+    ctx.wisv_destroy()
+
+
 def test_round_argument_errors_leave_outputs_untouched():
     dev = torch.device("cuda:0")
     w = W0
