@@ -45,7 +45,6 @@ struct AttnArgs {
 template <int NQ, int NW, bool FUSE>
 __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
-    constexpr int MERGE_BYTES = NW * NQ * (2 * 16 * 4 + 8 * 64 * 16);   // the end-of-kernel merge area comes first
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, bj = lane & 15, bg = lane >> 4;
     const int m0 = b * a.K;
@@ -77,7 +76,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     constexpr bool Q_IN_LDS = NQ > 1 || FUSE;
     constexpr int QREG = NQ > 1 ? 1 : NQ;
     u32x4 qhi[QREG][4], qlo[QREG][4];
-    u32x4 *qs = reinterpret_cast<u32x4 *>(lds + MERGE_BYTES);   // [NQ][4][2][64] query operands
+    u32x4 *qs = reinterpret_cast<u32x4 *>(lds);   // [NQ][4][2][64] query operands; the merge at the end re-uses the space
     int s = s_begin + wave;
     if (FUSE) {
         // this wave's first step is requested now; if it holds appended rows it is requested again below
@@ -316,6 +315,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     //      wave order.  LDS: sm, sl [NW][NQ][16] floats, then so [NW][NQ][8][64] floatx4.
     float *sm = reinterpret_cast<float *>(lds), *sl = sm + NW * NQ * 16;
     floatx4 *so = reinterpret_cast<floatx4 *>(sl + NW * NQ * 16);
+    __syncthreads();   // every wave is done with the query operands that live in the same LDS
     if (bg == 0) {
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
@@ -384,8 +384,8 @@ __global__ void k_attn_combine(const float *__restrict__ po, const float *__rest
 }
 
 template <int NQ, int NW, bool FUSE> static bool launch_nq(Ctx *c, const AttnArgs &a, dim3 grid) {
-    // merge area + parked query operands
-    const size_t lds = (size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16) + (NQ > 1 || FUSE ? (size_t)NQ * 8 * 1024 : 0);
+    // the merge area at the end of the kernel, which also holds the parked query operands before that
+    const size_t lds = std::max((size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16), (size_t)NQ * 8 * 1024);
     static bool opted_in = false;
     if (lds > 64 * 1024 && !opted_in) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_mfma<NQ, NW, FUSE>),

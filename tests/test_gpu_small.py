@@ -285,6 +285,25 @@ def test_small_bf16_decoder_prefill(batch, ctx_len, k, protos):
     _run_workload(w, TOL_BF16, kv="prefill")
 
 
+MID128 = replace(MID, head_dim=128, n_heads=4, n_kv_heads=1)     # the MFMA attention kernel needs head_dim 128
+
+
+@pytest.mark.parametrize("batch,ctx_len,k,kv", [
+    (1, 77, 1, "prefill"),      # one query row; a context that ends inside a 32-key step
+    (1, 130, 12, "prefill"),    # 48 query rows per KV head: three query tiles
+    (1, 95, 16, "synthetic"),   # 64 query rows: four query tiles, the largest block
+    (5, 61, 9, "synthetic"),    # 45 rows: the many-rows GEMM with one 64-row tile
+    (9, 40, 8, "prefill"),      # 72 rows: a ragged 128-row tile met by 4 x 2 waves
+])
+def test_small_bf16_decoder_kernel_variants(batch, ctx_len, k, kv):
+    """Shapes that reach the kernel variants the five workloads do not: query tile counts 1 to 4, row counts
+    on both sides of the GEMM kernels' switch-over points, contexts that are not multiples of 32."""
+    protos = tuple(PROTO_FH if b % 2 == 0 else PROTO_SH for b in range(batch))
+    w = replace(configs.get(3), model=MID128, batch=batch, ctx=ctx_len, k=k, protos=protos, kv_source=kv,
+                name=f"mid128_b{batch}_l{ctx_len}_k{k}_{kv}", index=10 + k, taus=(0.5,))
+    _run_workload(w, TOL_BF16, kv=kv)
+
+
 def test_small_bf16_decoder_synthetic_kv():
     w = replace(configs.get(2), model=replace(MID, head_dim=128, n_heads=4, n_kv_heads=1), batch=2, ctx=1100, k=8,
                 protos=(PROTO_SH, PROTO_FH), name="mid_bf16_synthkv", index=8)
