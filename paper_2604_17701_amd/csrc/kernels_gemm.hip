@@ -393,7 +393,7 @@ __device__ __forceinline__ void mm_epilogue(const GemmArgs &g, floatx16 (&acc)[R
 template <int NT, int WM, int RP, int KC, int U, int EPI>
 __global__ __launch_bounds__(512) void k_gemm_mm(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
-    static_assert(KC % U == 0, "a chunk is a whole number of turns of the ring");
+    static_assert(U % KC == 0, "a turn of the ring is a whole number of chunks");
     constexpr int NW = 8, WN = NW / WM, RB = 2 * RP;
     constexpr int NTW = NT * WM;                          // 32-row tiles of the workgroup
     constexpr int OPS = KC * NTW * 2;                     // B operands of one plane in a chunk
@@ -466,40 +466,48 @@ __global__ __launch_bounds__(512) void k_gemm_mm(GemmArgs g) {
                                                            *reinterpret_cast<bf16x8 *>(&SRC[t]), acc[p][t], 0, 0, 0);
     u32x4 bv[2][NT];
 
+    // One chunk: CC (a compile-time number) places it in a turn of the weight ring, which spans U / KC chunks.
+    // The next chunk's activations are requested before this chunk's MFMAs and written to LDS after them; the
+    // write must wait for exactly these loads while the weight refills issued after them stay in flight, and
+    // the compiler can count those only if every path through the chunk issues the same number of loads.
+#define WISV_MM_CHUNK(ch, CC)                                                                                      \
+    {                                                                                                              \
+        __syncthreads(); /* chunk ch is in LDS; nobody still reads the buffer chunk ch + 1 goes to */             \
+        /* this wave's row tiles start at tile wm NT of the workgroup's */                                        \
+        const unsigned char *buf = lds + (size_t)((ch) & 1) * BUF + (size_t)(wm * NT) * 2048 + lane * 16;          \
+        const int kbase = (ch) * KC;                                                                               \
+        WISV_MM_STAGE_LOAD((ch) + 1)                                                                               \
+        _Pragma("unroll") for (int lt = 0; lt < KC; ++lt) {                                                        \
+            if (kbase + lt < ntile) { /* uniform; no load inside, so the load counts hold on every path */        \
+                WISV_MM_READ_B(4 * lt, bv[0])                                                                      \
+                _Pragma("unroll") for (int og = 0; og < 4; ++og) {                                                 \
+                    if (og < 3) { WISV_MM_READ_B(4 * lt + og + 1, bv[(og + 1) & 1]) }                              \
+                    __builtin_amdgcn_sched_barrier(0);                                                             \
+                    WISV_MM_GROUP(4 * lt + og, abuf[(CC) * KC + lt], bv[og & 1])                                   \
+                    __builtin_amdgcn_sched_barrier(0);                                                             \
+                }                                                                                                  \
+            }                                                                                                      \
+            /* refill the slot right after its use; past the end the last tile is re-read into a slot nobody uses */ \
+            _Pragma("unroll") for (int p = 0; p < RP; ++p) _Pragma("unroll") for (int op = 0; op < 2; ++op)        \
+                abuf[(CC) * KC + lt][p][op] = wp[p * wstep + (size_t)min(kbase + lt + U, ntile - 1) * 64 + 16 * op]; \
+            __builtin_amdgcn_sched_barrier(0);                                                                     \
+        }                                                                                                          \
+        WISV_MM_STAGE_STORE((ch) + 1)                                                                              \
+    }
+
+    constexpr int TURN = U / KC;   // chunks per turn of the ring
     const int nchunk = (ntile + KC - 1) / KC;
     WISV_MM_STAGE_LOAD(0)
     WISV_MM_STAGE_STORE(0)
-    for (int ch = 0; ch < nchunk; ++ch) {
-        __syncthreads();   // chunk ch is in LDS; nobody still reads the buffer chunk ch + 1 goes to
-        // this wave's row tiles start at tile wm NT of the workgroup's
-        const unsigned char *buf = lds + (size_t)(ch & 1) * BUF + (size_t)(wm * NT) * 2048 + lane * 16;
-        const int kbase = ch * KC;
-        // the next chunk's activations are requested before this chunk's MFMAs and written to LDS after them; the
-        // write must wait for exactly these loads while the weight refills issued after them stay in flight, and
-        // the compiler can count those only if every path through the chunk issues the same number of loads
-        WISV_MM_STAGE_LOAD(ch + 1)
+    int ch = 0;
+    for (; ch + TURN <= nchunk; ch += TURN) {   // whole turns: no branch around any load
 #pragma unroll
-        for (int lt = 0; lt < KC; ++lt) {
-            if (kbase + lt < ntile) {   // uniform; no load inside, so the load counts below hold on every path
-                WISV_MM_READ_B(4 * lt, bv[0])
-#pragma unroll
-                for (int og = 0; og < 4; ++og) {
-                    if (og < 3) { WISV_MM_READ_B(4 * lt + og + 1, bv[(og + 1) & 1]) }
-                    __builtin_amdgcn_sched_barrier(0);
-                    WISV_MM_GROUP(4 * lt + og, abuf[lt % U], bv[og & 1])
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            // refill the slot right after its use; past the end the last tile is re-read into a slot nobody uses
-#pragma unroll
-            for (int p = 0; p < RP; ++p)
-#pragma unroll
-                for (int op = 0; op < 2; ++op)
-                    abuf[lt % U][p][op] = wp[p * wstep + (size_t)min(kbase + lt + U, ntile - 1) * 64 + 16 * op];
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        WISV_MM_STAGE_STORE(ch + 1)
+        for (int cc = 0; cc < TURN; ++cc) WISV_MM_CHUNK(ch + cc, cc)
     }
+#pragma unroll
+    for (int cc = 0; cc < TURN - 1; ++cc)       // the last, partial turn
+        if (ch + cc < nchunk) WISV_MM_CHUNK(ch + cc, cc)
+#undef WISV_MM_CHUNK
 #undef WISV_MM_STAGE_LOAD
 #undef WISV_MM_STAGE_STORE
 #undef WISV_MM_READ_B
