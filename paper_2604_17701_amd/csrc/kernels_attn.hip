@@ -372,13 +372,13 @@ __global__ void k_attn_combine(const float *__restrict__ po, const float *__rest
     float mx = -INFINITY;
     for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, pm[((size_t)s * rows + m) * H + h]);
     float num = 0.f, den = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
+#pragma unroll 8
+    for (int s = 0; s < n_splits; ++s) {   // no branch around the loads: an empty split weighs zero
         const size_t row = ((size_t)s * rows + m) * H + h;
-        const float ms = pm[row];
-        if (ms == -INFINITY) continue;
-        const float w = expf(ms - mx);
-        den = fmaf(w, pl[row], den);
-        num = fmaf(w, po[row * HD + d], num);
+        const float ms = pm[row], ls = pl[row], os = po[row * HD + d];
+        const float w = ms == -INFINITY ? 0.f : expf(ms - mx);
+        den = fmaf(w, ms == -INFINITY ? 0.f : ls, den);
+        num = fmaf(w, ms == -INFINITY ? 0.f : os, num);
     }
     act_store(o, ((size_t)m * H + h) * HD + d, num / den);
 }
@@ -397,16 +397,17 @@ template <int NQ, int NW, bool FUSE> static bool launch_nq(Ctx *c, const AttnArg
     return true;
 }
 
-// One workgroup per (stream, KV head) when that fills the chip or the context is short (then the workgroup
+// One workgroup per (stream, KV head) when that fills the chip or the context is short - at most four steps per
+// wave - (then the workgroup
 // writes the output itself, and can do RoPE and the cache append on the way in); otherwise k-splits of at
-// least four 32-key steps per wave.  0: the shape is not served.
+// least two 32-key steps per wave.  0: the shape is not served.
 static int attn_splits(const Ctx *c, const Fwd &f) {
     const wisv_config &g = c->cfg;
     const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
     if (!c->bf16 || g.head_dim != HD || R > 64 || f.rows != f.batch * f.k) return 0;
     const int nw = R <= 32 ? 8 : 4;
     const int n_steps = (f.max_len_ub + STEP - 1) / STEP, wgs = f.batch * g.n_kv_heads;
-    const int want = wgs >= 256 ? 1 : std::min((512 + wgs - 1) / wgs, (n_steps + 4 * nw - 1) / (4 * nw));
+    const int want = wgs >= 256 || n_steps <= 4 * nw ? 1 : std::min((512 + wgs - 1) / wgs, (n_steps + 2 * nw - 1) / (2 * nw));
     return std::max(1, std::min(want, c->att_max_splits));
 }
 
