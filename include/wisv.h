@@ -94,7 +94,8 @@ typedef struct {
     int32_t max_ctx;       /* KV positions per slot, drafted block included */
     int32_t max_k;         /* largest k of a round, <= WISV_MAX_K */
     int32_t device_id;
-    void *hip_stream; /* hipStream_t all work is enqueued on (borrowed; NULL = the null stream) */
+    void *hip_stream; /* hipStream_t all work is enqueued on (borrowed).  NULL: the ctx creates a stream of its own
+                         (an ordinary blocking stream: it orders itself against the null stream both ways) */
     void *kv_cache;   /* device pointer to borrowed cache memory, or NULL: the ctx allocates.
                          Layout [n_layers][max_batch][2 (K,V)][n_kv_heads] planes of ctx_pad * head_dim elements,
                          ctx_pad = max_ctx rounded up to a multiple of 32, dtype as above.
