@@ -587,7 +587,6 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
     return true;
 }
 
-// More than 16 rows: k_gemm_mm.  Row tiles of 16 NT rows with the least padding, about one workgroup per CU.
 constexpr int MM_RP = 2;            // pairs of row-blocks per wave of k_gemm_mm
 constexpr int MM_RB = 2 * MM_RP;
 
@@ -610,17 +609,30 @@ static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
     return true;
 }
 
-// Row tiles of k_gemm_mm: up to 64 rows one tile met by all eight waves (each 64 weight rows), beyond that
-// tiles of 128 rows met by 4 x 2 waves.  Returns the number of row tiles and of row-blocks a workgroup covers.
-static int mm_shape(int rows, int *rb_per_wg) {
-    *rb_per_wg = rows <= 64 ? 8 * MM_RB : 4 * MM_RB;
+// Workgroup shapes of k_gemm_mm.  Up to 64 rows: one row tile met by all eight waves (each 64 weight rows).
+// Beyond: tiles of 128 rows, met either by 4 x 2 waves (256 weight rows per workgroup, every weight tile loaded by
+// two waves) or - "wide" - by 8 x 1 waves with four row tiles each (512 weight rows, half the L2 traffic per
+// flop, but half as many workgroups).  Wide pays when it still fills the chip (>= 200 workgroups) and, with
+// k-splits, a split keeps >= 24 k-tiles.
+static bool mm_wide(int rows, int nrb, int nkt, bool can_split, int max_splits) {
+    if (rows <= 64) return false;
+    const int base = ((nrb + 8 * MM_RB - 1) / (8 * MM_RB)) * ((rows + 127) / 128);
+    if (!can_split) return base >= 200;
+    const int s = std::max(1, std::min(256 / std::max(1, base), max_splits));
+    return base * s >= 200 && nkt / s >= 24;
+}
+
+// returns the number of row tiles and of row-blocks a workgroup covers
+static int mm_shape(int rows, bool wide, int *rb_per_wg) {
+    *rb_per_wg = rows <= 64 || wide ? 8 * MM_RB : 4 * MM_RB;
     return rows <= 64 ? 1 : (rows + 127) / 128;
 }
 
 // More than 16 rows: k_gemm_mm
-template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits) {
+template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits, bool wide) {
     if (g.M <= 32) return launch_mm_t<1, 1, 2, 2, EPI>(c, g, splits);
     if (g.M <= 64) return launch_mm_t<2, 1, 2, 2, EPI>(c, g, splits);
+    if (wide) return launch_mm_t<4, 1, 2, 2, EPI>(c, g, splits);
     return launch_mm_t<2, 2, 2, 2, EPI>(c, g, splits);
 }
 
@@ -644,6 +656,7 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     fill_args(g, Wt, X, rows, n, kd);
     g.Yp = Yp; g.split_stride = split_stride;
     int s;
+    bool wide = false;
     if (rows <= 16) {
         // one row-block per wave: split k until about 4096 waves stream, a wave keeps at least 8 k-tiles
         s = (4096 + g.nrb - 1) / g.nrb;
@@ -651,14 +664,15 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     } else {
         // about one workgroup per CU over (row-block groups) x (row tiles) x splits; a split keeps >= 8 k-tiles
         int rb_per_wg;
-        const int tiles = mm_shape(rows, &rb_per_wg);
+        wide = mm_wide(rows, g.nrb, g.nkt, true, std::min(max_splits, std::max(1, g.nkt / 8)));
+        const int tiles = mm_shape(rows, wide, &rb_per_wg);
         const int base = ((g.nrb + rb_per_wg - 1) / rb_per_wg) * tiles;
         s = std::max(1, std::min(256 / std::max(1, base), std::min(max_splits, std::max(1, g.nkt / 8))));
     }
     g.kt_per_split = (g.nkt + s - 1) / s;
     const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
     const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
-                               : launch_ws_many<EPI_PARTIAL>(c, g, splits);
+                               : launch_ws_many<EPI_PARTIAL>(c, g, splits, wide);
     return ok ? splits : 0;
 }
 
@@ -673,7 +687,7 @@ bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf
     g.kt_per_split = g.nkt;
     g.H = H;
     if (rows <= 16) return launch_ws_t<1, 1, 8, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
-    return launch_ws_many<EPI_SWIGLU>(c, g, 1);
+    return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_wide(rows, g.nrb, g.nkt, false, 1));
 }
 
 // LM head with the argmax fused: greedy token of every row in c->amax; logits kept only on request
@@ -688,7 +702,7 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     {
         ProfScope ps(c, kclass);
         const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 8, EPI_ARGMAX>(c, g, 1, 70 * 1024)
-                                   : launch_ws_many<EPI_ARGMAX>(c, g, 1);
+                                   : launch_ws_many<EPI_ARGMAX>(c, g, 1, mm_wide(rows, g.nrb, g.nkt, false, 1));
         if (!ok) return false;
     }
     {
