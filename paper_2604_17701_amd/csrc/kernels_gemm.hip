@@ -388,13 +388,13 @@ __device__ __forceinline__ void mm_epilogue(const GemmArgs &g, floatx16 (&acc)[R
     }
 }
 
-// NT: 32-row tiles per wave; WM: waves along the rows (8 / WM along the row-blocks); RP: pairs of row-blocks
+// NT: 32-row tiles per wave; NW waves, WM of them along the rows (NW / WM along the row-blocks); RP: pairs of row-blocks
 // per wave; KC: k-tiles per LDS chunk; U: register slots of the weight stream
-template <int NT, int WM, int RP, int KC, int U, int EPI>
-__global__ __launch_bounds__(512) void k_gemm_mm(GemmArgs g) {
+template <int NT, int WM, int NW, int RP, int KC, int U, int EPI>
+__global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
     static_assert(U % KC == 0, "a turn of the ring is a whole number of chunks");
-    constexpr int NW = 8, WN = NW / WM, RB = 2 * RP;
+    constexpr int WN = NW / WM, RB = 2 * RP;
     constexpr int NTW = NT * WM;                          // 32-row tiles of the workgroup
     constexpr int OPS = KC * NTW * 2;                     // B operands of one plane in a chunk
     constexpr int PER_WAVE = (2 * OPS + NW - 1) / NW;     // operand loads a wave issues per chunk (both planes)
@@ -590,50 +590,54 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
 constexpr int MM_RP = 2;            // pairs of row-blocks per wave of k_gemm_mm
 constexpr int MM_RB = 2 * MM_RP;
 
-template <int NT, int WM, int KC, int U, int EPI>
+template <int NT, int WM, int NW, int KC, int U, int EPI>
 static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
-    constexpr int WN = 8 / WM, NTW = NT * WM;
+    constexpr int WN = NW / WM, NTW = NT * WM;
     g.gx = (g.nrb + WN * MM_RB - 1) / (WN * MM_RB);
     g.gz = (g.M + 32 * NTW - 1) / (32 * NTW);
     g.gs = splits;
     const size_t lds = (size_t)2 * 2 * KC * NTW * 2 * 1024;   // two buffers, two planes, 2 operands per (k-tile, row tile)
     static bool opted_in = false;     // per instantiation
     if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, MM_RP, KC, U, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, MM_RP, KC, U, EPI>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return false;
         opted_in = true;
     }
     const unsigned grid = (unsigned)((g.gx * g.gs + 7) / 8 * 8 * g.gz);
-    hipLaunchKernelGGL((k_gemm_mm<NT, WM, MM_RP, KC, U, EPI>), dim3(grid), dim3(512), lds, c->stream, g);
+    hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, MM_RP, KC, U, EPI>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
     return true;
 }
 
 // Workgroup shapes of k_gemm_mm.  Up to 64 rows: one row tile met by all eight waves (each 64 weight rows).
-// Beyond: tiles of 128 rows, met either by 4 x 2 waves (256 weight rows per workgroup, every weight tile loaded by
-// two waves) or - "wide" - by 8 x 1 waves with four row tiles each (512 weight rows, half the L2 traffic per
-// flop, but half as many workgroups).  Wide pays when it still fills the chip (>= 200 workgroups) and, with
-// k-splits, a split keeps >= 24 k-tiles.
-static bool mm_wide(int rows, int nrb, int nkt, bool can_split, int max_splits) {
-    if (rows <= 64) return false;
-    const int base = ((nrb + 8 * MM_RB - 1) / (8 * MM_RB)) * ((rows + 127) / 128);
-    if (!can_split) return base >= 200;
-    const int s = std::max(1, std::min(256 / std::max(1, base), max_splits));
-    return base * s >= 200 && nkt / s >= 24;
+// Beyond: tiles of 128 rows, met by 4 x 2 waves (256 weight rows per workgroup, every weight tile loaded by two
+// waves), or - "wide" - by 8 x 1 waves with four row tiles each (512 weight rows, half the L2 traffic per flop,
+// but half as many workgroups), or - "narrow" - by 2 x 2 waves (128 weight rows; two workgroups share a CU).
+// Wide pays when it still fills the chip (>= 200 workgroups) and, with k-splits, a split keeps >= 24 k-tiles;
+// narrow when a product without k-splits would otherwise leave CUs idle.
+enum { MM_NARROW = 0, MM_NORMAL = 1, MM_WIDE = 2 };   // 2 x 2, 4 x 2, 8 x 1 waves for more than 64 rows
+static int mm_layout(int rows, int nrb, int nkt, bool can_split, int max_splits) {
+    if (rows <= 64) return MM_NORMAL;
+    const int tiles = (rows + 127) / 128;
+    const int base8 = ((nrb + 8 * MM_RB - 1) / (8 * MM_RB)) * tiles, base4 = ((nrb + 4 * MM_RB - 1) / (4 * MM_RB)) * tiles;
+    if (!can_split) return base8 >= 200 ? MM_WIDE : base4 >= 200 ? MM_NORMAL : MM_NARROW;
+    const int s = std::max(1, std::min(256 / std::max(1, base8), max_splits));
+    return base8 * s >= 200 && nkt / s >= 24 ? MM_WIDE : MM_NORMAL;
 }
 
 // returns the number of row tiles and of row-blocks a workgroup covers
-static int mm_shape(int rows, bool wide, int *rb_per_wg) {
-    *rb_per_wg = rows <= 64 || wide ? 8 * MM_RB : 4 * MM_RB;
+static int mm_shape(int rows, int layout, int *rb_per_wg) {
+    *rb_per_wg = (rows <= 64 || layout == MM_WIDE ? 8 : layout == MM_NORMAL ? 4 : 2) * MM_RB;
     return rows <= 64 ? 1 : (rows + 127) / 128;
 }
 
 // More than 16 rows: k_gemm_mm
-template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits, bool wide) {
-    if (g.M <= 32) return launch_mm_t<1, 1, 2, 2, EPI>(c, g, splits);
-    if (g.M <= 64) return launch_mm_t<2, 1, 2, 2, EPI>(c, g, splits);
-    if (wide) return launch_mm_t<4, 1, 2, 2, EPI>(c, g, splits);
-    return launch_mm_t<2, 2, 2, 2, EPI>(c, g, splits);
+template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits, int layout) {
+    if (g.M <= 32) return launch_mm_t<1, 1, 8, 2, 2, EPI>(c, g, splits);
+    if (g.M <= 64) return launch_mm_t<2, 1, 8, 2, 2, EPI>(c, g, splits);
+    if (layout == MM_WIDE) return launch_mm_t<4, 1, 8, 2, 2, EPI>(c, g, splits);
+    if (layout == MM_NARROW) return launch_mm_t<2, 2, 4, 2, 2, EPI>(c, g, splits);
+    return launch_mm_t<2, 2, 8, 2, 2, EPI>(c, g, splits);
 }
 
 bool ws_supported(const Ctx *c, int rows, int kd) {
@@ -656,7 +660,7 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     fill_args(g, Wt, X, rows, n, kd);
     g.Yp = Yp; g.split_stride = split_stride;
     int s;
-    bool wide = false;
+    int layout = MM_NORMAL;
     if (rows <= 16) {
         // one row-block per wave: split k until about 4096 waves stream, a wave keeps at least 8 k-tiles
         s = (4096 + g.nrb - 1) / g.nrb;
@@ -664,15 +668,15 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     } else {
         // about one workgroup per CU over (row-block groups) x (row tiles) x splits; a split keeps >= 8 k-tiles
         int rb_per_wg;
-        wide = mm_wide(rows, g.nrb, g.nkt, true, std::min(max_splits, std::max(1, g.nkt / 8)));
-        const int tiles = mm_shape(rows, wide, &rb_per_wg);
+        layout = mm_layout(rows, g.nrb, g.nkt, true, std::min(max_splits, std::max(1, g.nkt / 8)));
+        const int tiles = mm_shape(rows, layout, &rb_per_wg);
         const int base = ((g.nrb + rb_per_wg - 1) / rb_per_wg) * tiles;
         s = std::max(1, std::min(256 / std::max(1, base), std::min(max_splits, std::max(1, g.nkt / 8))));
     }
     g.kt_per_split = (g.nkt + s - 1) / s;
     const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
     const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
-                               : launch_ws_many<EPI_PARTIAL>(c, g, splits, wide);
+                               : launch_ws_many<EPI_PARTIAL>(c, g, splits, layout);
     return ok ? splits : 0;
 }
 
@@ -687,7 +691,7 @@ bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf
     g.kt_per_split = g.nkt;
     g.H = H;
     if (rows <= 16) return launch_ws_t<1, 1, 8, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
-    return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_wide(rows, g.nrb, g.nkt, false, 1));
+    return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1));
 }
 
 // LM head with the argmax fused: greedy token of every row in c->amax; logits kept only on request
@@ -702,7 +706,7 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     {
         ProfScope ps(c, kclass);
         const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 8, EPI_ARGMAX>(c, g, 1, 70 * 1024)
-                                   : launch_ws_many<EPI_ARGMAX>(c, g, 1, mm_wide(rows, g.nrb, g.nkt, false, 1));
+                                   : launch_ws_many<EPI_ARGMAX>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1));
         if (!ok) return false;
     }
     {
