@@ -90,6 +90,24 @@ def measured_traffic(workload, kclass):
     return bytes_ / launches, f"profiles/{workload}_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE scaled by a copy kernel)"
 
 
+def link_model_rows(w, t_edge, res):
+    """The paper's per-round latency model (Sec. IV) with this run's measured edge time T_T + T_J plugged in, on
+    two example links: which upload option the model prefers, and the modelled communication + edge latency
+    of a round for both (the drafter term is left out: it is the same for both options)."""
+    from paper_2604_17701_amd import link_model as lm
+    fr = lm.Framing(vocab=w.model.vocab, d_hidden=w.model.d_draft, bits_hidden=16, hdr_up=256, hdr_down=256, bits_pos=8)
+    m = float(sum(bin(int(x)).count("1") for x in res["mismatch_mask"])) / max(len(res["mismatch_mask"]), 1)
+    rows = []
+    for name, link in (("50/100 Mbit/s, 2 ms", lm.Link(50e6, 100e6, 0.01, 0.01, 2e-3)),
+                       ("50/100 Mbit/s, 20 ms", lm.Link(50e6, 100e6, 0.01, 0.01, 20e-3))):
+        fh = lm.t_comm_fh(fr, link, w.k) + t_edge
+        sh = (link.t_up(fr.b_up1_sh(w.k)) + link.t_down(fr.hdr_down + m * fr.bits_pos) + link.t_up(fr.hdr_up + m * fr.b_hid) +
+              link.t_down(fr.b_fb) + 2 * link.tau_rtt) + t_edge
+        rows.append({"link": name, "mean_requested_positions": m, "T_FH_ms": fh * 1e3, "T_SH_ms": sh * 1e3,
+                     "model_prefers": "FH" if lm.choose_protocol(fr, link, w.k, m) == lm.PROTO_FH else "SH"})
+    return rows
+
+
 def cpu_baseline(w, weights_dev, inputs, gen, np, torch, budget_s=20.0):
     """The oracle, as it stands, on the host cores: whole rounds of stream 0 of the same workload."""
     from oracle import wisv_oracle as wo
@@ -202,6 +220,13 @@ def main():
                 "event_pair_overhead_us": pair_us,
                 "timing": f"HIP event pair around every launch on the round's stream, {a.steps} rounds right after the timed ones, "
                           "minus the duration of an empty event pair"}
+    # matrix-core work of the three GEMM classes: algorithmic FLOP (2 x rows x weights) and what the two-term
+    # activations make the MFMA units execute (twice that), against the dense bf16 peak
+    gemm_ms = sum(kernels[n]["ms_per_round"] for n in ("gemm_gate_up", "gemm_qkv_o_down", "lm_head") if n in kernels)
+    gemm_flop = 2.0 * w.m * sum(alg_bytes[n] for n in ("gemm_gate_up", "gemm_qkv_o_down", "lm_head")) / esz
+    gemm_mfma = {"algorithmic_TFLOPs": gemm_flop / (gemm_ms * 1e-3) / 1e12, "executed_TFLOPs": 2 * gemm_flop / (gemm_ms * 1e-3) / 1e12,
+                 "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "executed_frac_of_peak": 2 * gemm_flop / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                 "gemm_ms_per_round": gemm_ms} if gemm_ms > 0 and m.dtype == "bf16" else None
     round_alg = w.algorithmic_bytes()
     out = {
         "metric": "verified draft tokens/sec + ms per verify round, 8B-shaped target, K=4",
@@ -217,6 +242,8 @@ def main():
         "accepted_tokens_per_s": float(res["accepted_len"].sum()) / (ms * 1e-3),
         "committed_tokens_per_s": float((res["accepted_len"] + 1).sum()) / (ms * 1e-3),
         "mean_accepted_len": float(res["accepted_len"].mean()),
+        "gemm_mfma": gemm_mfma,
+        "link_model": link_model_rows(w, ms * 1e-3, res),
         "kernels": kernels,
     }
     if not a.no_cpu_baseline:
