@@ -365,20 +365,38 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     }
 }
 
-// o[m][h][:] = sum_s e^(m_s - m*) O_s / sum_s e^(m_s - m*) l_s, splits in index order; one block per (row, head)
+// o[m][h][:] = sum_s e^(m_s - m*) O_s / sum_s e^(m_s - m*) l_s, splits in index order; one block per (row, head).
+// Splits are taken BATCH at a time, all loads of a batch issued before the first is used (slots past the last
+// split re-read it and weigh zero), batches chained with the same rescaling rule.
+template <int BATCH>
 __global__ void k_attn_combine(const float *__restrict__ po, const float *__restrict__ pm, const float *__restrict__ pl,
                                int n_splits, int rows, int H, ActBuf o) {
     const int m = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-    float mx = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, pm[((size_t)s * rows + m) * H + h]);
-    float num = 0.f, den = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < n_splits; ++s) {   // no branch around the loads: an empty split weighs zero
-        const size_t row = ((size_t)s * rows + m) * H + h;
-        const float ms = pm[row], ls = pl[row], os = po[row * HD + d];
-        const float w = ms == -INFINITY ? 0.f : expf(ms - mx);
-        den = fmaf(w, ms == -INFINITY ? 0.f : ls, den);
-        num = fmaf(w, ms == -INFINITY ? 0.f : os, num);
+    float mx = -INFINITY, num = 0.f, den = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += BATCH) {
+        float ms[BATCH], ls[BATCH], os[BATCH];
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const size_t row = ((size_t)min(s0 + i, n_splits - 1) * rows + m) * H + h;
+            ms[i] = pm[row];
+            ls[i] = pl[row];
+            os[i] = po[row * HD + d];
+        }
+        float bmx = mx;
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) bmx = fmaxf(bmx, s0 + i < n_splits ? ms[i] : -INFINITY);
+        if (bmx == -INFINITY) continue;
+        const float keep = mx == -INFINITY ? 0.f : expf(mx - bmx);
+        num *= keep;
+        den *= keep;
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const bool on = s0 + i < n_splits && ms[i] != -INFINITY;
+            const float w = on ? expf(ms[i] - bmx) : 0.f;
+            den = fmaf(w, on ? ls[i] : 0.f, den);
+            num = fmaf(w, on ? os[i] : 0.f, num);
+        }
+        mx = bmx;
     }
     act_store(o, ((size_t)m * H + h) * HD + d, num / den);
 }
@@ -446,8 +464,12 @@ bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial) {
     }
     if (a.n_splits > 1) {
         ProfScope ps(c, KC_ATTN_COMBINE);
-        hipLaunchKernelGGL(k_attn_combine, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
-                           a.n_splits, f.rows, g.n_heads, c->o);
+        if (a.n_splits <= 4)
+            hipLaunchKernelGGL(k_attn_combine<4>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
+                               a.n_splits, f.rows, g.n_heads, c->o);
+        else
+            hipLaunchKernelGGL(k_attn_combine<16>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
+                               a.n_splits, f.rows, g.n_heads, c->o);
     }
     return true;
 }
