@@ -157,16 +157,35 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
 
     // ---- queries as MFMA B operands (two bf16 terms): lane (bj, bg) holds Q[rho = 16 nq + bj][32 t + 8 bg ..].
     //      One query tile lives in registers; more would crowd out the accumulators, so they are parked in LDS
-    //      (every wave builds the same operands; wave 0 stores them) and re-read at each use.
+    //      (built once, shared by the waves) and re-read at each use.
     if (!FUSE) {
+        if (NQ > 1) {
+            // the NQ x 4 operand pairs are dealt to the waves; rows past R load row 0 (no branch around the loads)
+            // and become zero
+            for (int item = wave; item < NQ * 4; item += NW) {
+                const int nq = item >> 2, t = item & 3, rho = nq * 16 + bj;
+                const bool valid = rho < R;
+                const float *qp = a.q + ((size_t)(m0 + (valid ? rho / a.rep : 0)) * a.H + (size_t)g * a.rep + (valid ? rho % a.rep : 0)) * HD;
+                const float4 x0 = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg);
+                const float4 x1 = *reinterpret_cast<const float4 *>(qp + 32 * t + 8 * bg + 4);
+                const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                uint32_t h[4], l[4];
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            const int rho = nq * 16 + bj;
-            const bool valid = rho < R;
-            const float *qp = a.q + ((size_t)(m0 + (valid ? rho / a.rep : 0)) * a.H + (size_t)g * a.rep + (valid ? rho % a.rep : 0)) * HD;
-            if (NQ > 1 && wave != 0) continue;
-            // all eight loads first, then the arithmetic; rows past R load row 0 (no branch around the loads) and
-            // become zero
+                for (int e = 0; e < 4; ++e) {
+                    bf16_t h0, l0, h1, l1;
+                    split2(valid ? xs[2 * e] : 0.f, h0, l0);
+                    split2(valid ? xs[2 * e + 1] : 0.f, h1, l1);
+                    h[e] = h0 | ((uint32_t)h1 << 16);
+                    l[e] = l0 | ((uint32_t)l1 << 16);
+                }
+                qs[(item * 2 + 0) * 64 + lane] = u32x4{h[0], h[1], h[2], h[3]};
+                qs[(item * 2 + 1) * 64 + lane] = u32x4{l[0], l[1], l[2], l[3]};
+            }
+            __syncthreads();
+        } else {
+            const bool valid = bj < R;
+            const float *qp = a.q + ((size_t)(m0 + (valid ? bj / a.rep : 0)) * a.H + (size_t)g * a.rep + (valid ? bj % a.rep : 0)) * HD;
+            // all eight loads first, then the arithmetic
             float4 xq[4][2];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
@@ -187,16 +206,10 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
                     h[e] = h0 | ((uint32_t)h1 << 16);
                     l[e] = l0 | ((uint32_t)l1 << 16);
                 }
-                if (NQ > 1) {
-                    qs[((nq * 4 + t) * 2 + 0) * 64 + lane] = u32x4{h[0], h[1], h[2], h[3]};
-                    qs[((nq * 4 + t) * 2 + 1) * 64 + lane] = u32x4{l[0], l[1], l[2], l[3]};
-                } else {
-                    qhi[0][t] = u32x4{h[0], h[1], h[2], h[3]};
-                    qlo[0][t] = u32x4{l[0], l[1], l[2], l[3]};
-                }
+                qhi[0][t] = u32x4{h[0], h[1], h[2], h[3]};
+                qlo[0][t] = u32x4{l[0], l[1], l[2], l[3]};
             }
         }
-        if (NQ > 1) __syncthreads();
     } else if (NQ == 1) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
