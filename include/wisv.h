@@ -172,6 +172,55 @@ int wisv_ctx_create(const wisv_config *config, const wisv_weights *weights, wisv
  * The target's greedy token for draft position 0 is the stream's pred_next state. */
 int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_round_out *out);
 
+/* --- speculative-sampling verification ----------------------------------------------------------
+ * The stochastic verifier of Sec. II-A on the same target forward: position j of a block is accepted with
+ * probability alpha_j = min{1, p_T(y_j) / p_D(y_j)} (eq. ss_accept_prob), positions are taken in order until the
+ * first rejection, and the token emitted there is drawn from the residual distribution proportional to
+ * p_T - alpha p_D = max(0, p_T - p_D) (eq. ss_residual); when all k are accepted the emitted token is drawn from
+ * the target distribution after the block.  p_T is the softmax of the target's logits (temperature 1).
+ *
+ * The random numbers are inputs: position j is accepted iff u_accept < alpha_j, and the emitted token is the
+ * smallest token id whose cumulative weight exceeds u_sample times the total weight.
+ * Position 0 of a block is the stream's pending token (pred_next: the token the previous round emitted, whose
+ * K/V row this forward appends): its target distribution is the point mass there, so alpha_0 is 1 if
+ * draft_tokens[0] is that token and 0 otherwise, and a rejection at position 0 emits the pending token again.
+ * The drafter's distribution of position 0 is not read.  A drafted token with p_D = 0 is accepted.
+ * Arithmetic: float exponentials, double normalisers and cumulative sums in a fixed order (equal inputs give
+ * equal outputs); a decision that a rounding error of about 1e-7 relative could turn may differ from an exact
+ * evaluation. */
+typedef struct {
+    int32_t batch; /* 1..max_batch */
+    int32_t k;     /* 1..max_k */
+    const int32_t *stream_ids;   /* [batch] distinct slot indices */
+    const int32_t *draft_tokens; /* [batch*k] */
+    const float *draft_probs;    /* [batch*k, vocab]: row b*k + j is the drafter's distribution token j was drawn from
+                                    (nonnegative; rows with j = 0 are not read) */
+    const float *u_accept;       /* [batch*k] uniform numbers in [0, 1) */
+    const float *u_sample;       /* [batch] uniform numbers in [0, 1) */
+    uint32_t flags;              /* WISV_FLAG_NO_COMMIT, WISV_FLAG_DEVICE_IO */
+} wisv_ss_in;
+
+typedef struct {                 /* caller-owned; all required */
+    int32_t *accepted_len;     /* [batch] A in [0, k] */
+    int32_t *correction_token; /* [batch] the emitted token */
+    float *alpha;              /* [batch*k] acceptance probability of every position (also those after A) */
+} wisv_ss_out;
+
+/* One speculative-sampling round: the target forward of wisv_verify_round with all logits kept, then the rule
+ * above.  Host pointers, or device pointers with WISV_FLAG_DEVICE_IO (enqueue only).  Commit as in
+ * wisv_verify_round: each stream's length grows by A and its pending token becomes the emitted one.  In host
+ * mode the first call allocates a device staging buffer of max_batch * max_k * vocab floats for draft_probs. */
+int wisv_ss_verify_round(wisv_ctx *ctx, const wisv_ss_in *in, wisv_ss_out *out);
+
+/* The rule alone on logits the caller holds: all pointers are device pointers (16-byte aligned rows make the
+ * kernels use vector loads), nothing of the ctx's stream state is read or written, the work is enqueued on the
+ * ctx's stream.  logits [batch*k, vocab]: row b*k + j is the target's output after token j of stream b;
+ * pending_tokens [batch]; vocab at most the ctx's.  Outputs as in wisv_ss_out. */
+int wisv_ss_decide(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab, const float *logits,
+                   const int32_t *pending_tokens, const int32_t *draft_tokens, const float *draft_probs,
+                   const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *emitted_token,
+                   float *alpha);
+
 /* Frees everything the ctx owns (not the borrowed stream / cache).  NULL is a no-op. */
 int wisv_destroy(wisv_ctx *ctx);
 

@@ -28,7 +28,8 @@ WISV_MAX_K = 16
 
 EXPORTS = ("wisv_ctx_create", "wisv_verify_round", "wisv_destroy", "wisv_prefill", "wisv_set_state",
            "wisv_get_state", "wisv_kv_import", "wisv_kv_export", "wisv_debug_copy", "wisv_last_round_ms",
-           "wisv_profile_enable", "wisv_profile_collect", "wisv_profile_read", "wisv_calibration_copy", "wisv_last_error")
+           "wisv_profile_enable", "wisv_profile_collect", "wisv_profile_read", "wisv_calibration_copy", "wisv_last_error",
+           "wisv_ss_verify_round", "wisv_ss_decide")
 
 
 class WisvError(RuntimeError):
@@ -65,6 +66,15 @@ class wisv_round_out(C.Structure):
                                           "mismatch_mask", "status")]
 
 
+class wisv_ss_in(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("k", C.c_int32), ("stream_ids", C.c_void_p), ("draft_tokens", C.c_void_p),
+                ("draft_probs", C.c_void_p), ("u_accept", C.c_void_p), ("u_sample", C.c_void_p), ("flags", C.c_uint32)]
+
+
+class wisv_ss_out(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("accepted_len", "correction_token", "alpha")]
+
+
 _lib = None
 
 
@@ -93,6 +103,8 @@ def load_library() -> C.CDLL:
                                           C.POINTER(C.c_int64)]
         lib.wisv_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         lib.wisv_last_error.argtypes = [C.c_void_p]
+        lib.wisv_ss_verify_round.argtypes = [C.c_void_p, C.POINTER(wisv_ss_in), C.POINTER(wisv_ss_out)]
+        lib.wisv_ss_decide.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 9
         lib.wisv_last_error.restype = C.c_char_p
         for name in EXPORTS:
             if name != "wisv_last_error":
@@ -245,6 +257,49 @@ class Context:
         """Uploads one round's arguments once and returns a DeviceRound that re-enqueues it."""
         return DeviceRound(self, stream_ids, draft_tokens, proto, hd, hd_row, csi, tau, k, flags)
 
+    # ---------------------------------------------------------------- speculative sampling
+    def wisv_ss_verify_round(self, stream_ids, draft_tokens, draft_probs, u_accept, u_sample, k: int, flags: int = 0):
+        """Host-buffer speculative-sampling round.  draft_probs: float array [batch*k, vocab]."""
+        sid, toks = _host_i32(stream_ids), _host_i32(draft_tokens).reshape(-1)
+        b = sid.size
+        q, u, v = _host_f32(draft_probs), _host_f32(u_accept).reshape(-1), _host_f32(u_sample).reshape(-1)
+        if toks.size != b * k or q.size != b * k * self.model.vocab or u.size != b * k or v.size != b:
+            raise ValueError("round argument sizes do not match batch, k and the vocabulary")
+        out = {"accepted_len": np.zeros(b, np.int32), "correction_token": np.zeros(b, np.int32),
+               "alpha": np.zeros(b * k, np.float32)}
+        sin = wisv_ss_in(b, k, sid.ctypes.data, toks.ctypes.data, q.ctypes.data, u.ctypes.data, v.ctypes.data,
+                         flags & ~WISV_FLAG_DEVICE_IO)
+        sout = wisv_ss_out(*[out[n].ctypes.data for n in ("accepted_len", "correction_token", "alpha")])
+        self._check(self._lib.wisv_ss_verify_round(self._h, C.byref(sin), C.byref(sout)))
+        out["alpha"] = out["alpha"].reshape(b, k)
+        return out
+
+    def ss_device_round(self, stream_ids, draft_tokens, draft_probs, u_accept, u_sample, k: int, flags: int = 0):
+        """Uploads one speculative-sampling round's arguments once; the returned object's run() only enqueues."""
+        return SsDeviceRound(self, stream_ids, draft_tokens, draft_probs, u_accept, u_sample, k, flags)
+
+    def wisv_ss_decide(self, logits: torch.Tensor, pending_tokens: torch.Tensor, draft_tokens: torch.Tensor,
+                       draft_probs: torch.Tensor, u_accept: torch.Tensor, u_sample: torch.Tensor, k: int):
+        """The rule alone on device tensors: logits, draft_probs float [batch*k, vocab]; pending_tokens int32
+        [batch]; draft_tokens int32 [batch*k]; u_accept float [batch*k]; u_sample float [batch].
+        Returns device tensors (accepted_len, emitted_token, alpha); enqueue only."""
+        rows, vocab = logits.shape
+        b = rows // k
+        want = ((logits, torch.float32, rows * vocab), (draft_probs, torch.float32, rows * vocab),
+                (pending_tokens, torch.int32, b), (draft_tokens, torch.int32, rows), (u_accept, torch.float32, rows),
+                (u_sample, torch.float32, b))
+        for t, dt, n in want:
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and t.numel() == n):
+                raise ValueError("wisv_ss_decide takes contiguous CUDA tensors of the documented types and sizes")
+        alen = torch.zeros(b, dtype=torch.int32, device=logits.device)
+        tok = torch.zeros(b, dtype=torch.int32, device=logits.device)
+        alpha = torch.zeros(rows, dtype=torch.float32, device=logits.device)
+        torch.cuda.current_stream(logits.device).synchronize()   # the inputs may come from another stream
+        self._check(self._lib.wisv_ss_decide(self._h, b, k, vocab, logits.data_ptr(), pending_tokens.data_ptr(),
+                                             draft_tokens.data_ptr(), draft_probs.data_ptr(), u_accept.data_ptr(),
+                                             u_sample.data_ptr(), alen.data_ptr(), tok.data_ptr(), alpha.data_ptr()))
+        return alen, tok, alpha.view(b, k)
+
     # ---------------------------------------------------------------- state
     def wisv_prefill(self, stream_id: int, tokens):
         t = _host_i32(tokens)
@@ -351,6 +406,39 @@ class DeviceRound:
         r["target_argmax"] = r["target_argmax"].reshape(b, k + 1)
         r["mismatch_mask"] = r["mismatch_mask"].view(np.uint32)
         r["status"] = r["status"].view(np.uint32)
+        return r
+
+
+class SsDeviceRound:
+    """One speculative-sampling round with device-resident arguments: run() only enqueues kernels."""
+
+    def __init__(self, ctx: Context, stream_ids, draft_tokens, draft_probs, u_accept, u_sample, k: int, flags: int):
+        dev = ctx.device
+        self.ctx, self.k = ctx, k
+        i32 = lambda a: torch.from_numpy(_host_i32(a).reshape(-1)).to(dev)
+        f32 = lambda a: (a.detach().to(dev, torch.float32).contiguous().reshape(-1) if torch.is_tensor(a)
+                         else torch.from_numpy(_host_f32(a).reshape(-1)).to(dev))
+        self.sid, self.toks = i32(stream_ids), i32(draft_tokens)
+        b = self.batch = self.sid.numel()
+        self.q, self.u, self.v = f32(draft_probs), f32(u_accept), f32(u_sample)
+        if self.toks.numel() != b * k or self.q.numel() != b * k * ctx.model.vocab or self.u.numel() != b * k \
+                or self.v.numel() != b:
+            raise ValueError("round argument sizes do not match batch, k and the vocabulary")
+        self.out = {"accepted_len": torch.zeros(b, dtype=torch.int32, device=dev),
+                    "correction_token": torch.zeros(b, dtype=torch.int32, device=dev),
+                    "alpha": torch.zeros(b * k, dtype=torch.float32, device=dev)}
+        self.sin = wisv_ss_in(b, k, self.sid.data_ptr(), self.toks.data_ptr(), self.q.data_ptr(), self.u.data_ptr(),
+                              self.v.data_ptr(), flags | WISV_FLAG_DEVICE_IO)
+        self.sout = wisv_ss_out(*[self.out[n].data_ptr() for n in ("accepted_len", "correction_token", "alpha")])
+        torch.cuda.synchronize(dev)
+
+    def run(self):
+        self.ctx._check(self.ctx._lib.wisv_ss_verify_round(self.ctx._h, C.byref(self.sin), C.byref(self.sout)))
+
+    def results(self):
+        torch.cuda.synchronize(self.ctx.device)
+        r = {n: t.cpu().numpy() for n, t in self.out.items()}
+        r["alpha"] = r["alpha"].reshape(self.batch, self.k)
         return r
 
 

@@ -1,0 +1,241 @@
+// Speculative-sampling verification of drafted blocks (Sec. II-A: acceptance probability eq. ss_accept_prob,
+// residual distribution eq. ss_residual, applied position by position until the first rejection).
+//
+//   1. stats    per (logits row, chunk of the vocabulary): largest logit and sum of exp(logit - largest)
+//   2. accept   per stream: softmax normalisers of its rows, alpha_j of every position, the first rejected
+//               position A, and the distribution the emitted token is drawn from
+//   3. mass     per (stream, chunk): weight of the chunk under that distribution (residual or target)
+//   4. sample   per stream: the chunk, then the token, at which the cumulative weight passes v * total; commit
+//
+// Probabilities are float exponentials divided by a double normaliser; every sum that decides a token is a
+// double sum in a fixed order, so equal inputs give equal tokens.  HBM-bound: the logits are read twice for
+// one row per stream and once for the others, the drafter's distribution once for one row per stream.
+#include <algorithm>
+
+#include "wisv_internal.h"
+
+namespace wisv {
+
+constexpr int SS_THREADS = 256, SS_PER_THREAD = 8;
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// eight consecutive elements of a row starting at i0 (a multiple of 8); elements at or beyond n read as `fill`.
+// Every lane issues the same loads (clamped addresses), the selection comes afterwards.
+__device__ __forceinline__ void ss_load8(const float *__restrict__ row, int i0, int n, bool vec, float fill, float x[8]) {
+    if (vec) {   // n is a multiple of 4 and the row is 16-byte aligned
+        const int a = min(i0, n - 4), b = min(i0 + 4, n - 4);
+        const float4 lo = *reinterpret_cast<const float4 *>(row + a), hi = *reinterpret_cast<const float4 *>(row + b);
+        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
+        x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = i0 + e < n ? x[e] : fill;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = row[min(i0 + e, n - 1)];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = i0 + e < n ? x[e] : fill;
+    }
+}
+
+__global__ void __launch_bounds__(SS_THREADS)
+k_ss_stats(const float *__restrict__ logits, int V, int C, bool vec, float *__restrict__ pm, float *__restrict__ pz) {
+    __shared__ float red[SS_THREADS / 64];
+    const int c = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
+    float x[8];
+    ss_load8(logits + (size_t)r * V, (c * SS_THREADS + tid) * SS_PER_THREAD, V, vec, -INFINITY, x);
+    float m = x[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) m = fmaxf(m, x[e]);
+    m = wave_max(m);
+    if ((tid & 63) == 0) red[tid >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float z = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z += expf(x[e] - m);   // exp(-inf) = 0 beyond the row's end
+    z = wave_sum(z);
+    if ((tid & 63) == 0) red[tid >> 6] = z;
+    __syncthreads();
+    if (tid == 0) {
+        pm[(size_t)r * C + c] = m;
+        pz[(size_t)r * C + c] = (red[0] + red[1]) + (red[2] + red[3]);
+    }
+}
+
+// one wave per stream; lane j handles position j, lanes 1..k also the normaliser of logits row j - 1
+__global__ void __launch_bounds__(64)
+k_ss_accept(int k, int V, int C, int max_batch, const float *__restrict__ logits, const float *__restrict__ pm,
+            const float *__restrict__ pz, const int32_t *__restrict__ stream_ids, const int32_t *__restrict__ pred_next,
+            const int32_t *__restrict__ pending_tokens, const int32_t *__restrict__ tokens, const float *__restrict__ q,
+            const float *__restrict__ u, float *__restrict__ row_m, double *__restrict__ row_z, int32_t *__restrict__ sel_row,
+            int32_t *__restrict__ sel_mode, int32_t *__restrict__ alen, int32_t *__restrict__ ytok, float *__restrict__ alpha_out) {
+    const int b = blockIdx.x, j = threadIdx.x;
+    const int pending = pending_tokens ? pending_tokens[b] : pred_next[min(max(stream_ids[b], 0), max_batch - 1)];
+    bool reject = false;
+    if (j <= k) {
+        double alpha;
+        if (j == 0) {
+            alpha = tokens[b * k] == pending ? 1.0 : 0.0;
+        } else {
+            const int rp = b * k + j - 1;
+            float M = -INFINITY;
+            for (int c = 0; c < C; ++c) M = fmaxf(M, pm[(size_t)rp * C + c]);
+            double Z = 0.0;
+            for (int c = 0; c < C; ++c) Z += (double)pz[(size_t)rp * C + c] * (double)expf(pm[(size_t)rp * C + c] - M);
+            row_m[rp] = M;
+            row_z[rp] = Z;
+            alpha = 1.0;
+            if (j < k) {
+                const int t = min(max(tokens[rp + 1], 0), V - 1);
+                const double P = (double)expf(logits[(size_t)rp * V + t] - M) / Z, qv = (double)q[(size_t)(rp + 1) * V + t];
+                alpha = qv <= P ? 1.0 : P / qv;
+            }
+        }
+        if (j < k) {
+            alpha_out[b * k + j] = (float)alpha;
+            reject = !((double)u[b * k + j] < alpha);
+        }
+    }
+    const unsigned long long rej = __ballot(reject);
+    if (j == 0) {
+        const int A = rej ? __builtin_ctzll(rej) : k;
+        alen[b] = A;
+        sel_row[b] = b * k + max(A, 1) - 1;
+        sel_mode[b] = A == 0 ? 0 : A < k ? 1 : 2;    // 0: emit the pending token; 1: residual of position A; 2: target after the block
+        if (A == 0) ytok[b] = pending;
+    }
+}
+
+// weight of element i of the selected row: p_T(i), less min(p_D(i), p_T(i)) for a residual
+__device__ __forceinline__ double ss_weight(float x, float q, float M, double Z, bool resid) {
+    const double p = (double)expf(x - M) / Z;
+    return resid ? fmax(p - (double)q, 0.0) : p;
+}
+
+__global__ void __launch_bounds__(SS_THREADS)
+k_ss_mass(int V, int C, int rows, bool vec, const float *__restrict__ logits, const float *__restrict__ q,
+          const float *__restrict__ row_m, const double *__restrict__ row_z, const int32_t *__restrict__ sel_row,
+          const int32_t *__restrict__ sel_mode, double *__restrict__ mass) {
+    __shared__ double red[SS_THREADS / 64];
+    const int c = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int rs = sel_row[b], mode = sel_mode[b];
+    const int i0 = (c * SS_THREADS + tid) * SS_PER_THREAD;
+    float x[8], qv[8];
+    ss_load8(logits + (size_t)rs * V, i0, V, vec, -INFINITY, x);
+    ss_load8(q + (size_t)min(rs + 1, rows - 1) * V, i0, V, vec, 0.f, qv);
+    const float M = row_m[rs];
+    const double Z = row_z[rs];
+    double s = 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += ss_weight(x[e], qv[e], M, Z, mode == 1);
+    s = wave_sum_f64(s);
+    if ((tid & 63) == 0) red[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) mass[(size_t)b * C + c] = mode == 0 ? 0.0 : (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ void __launch_bounds__(SS_THREADS)
+k_ss_sample(int V, int C, int rows, int max_batch, bool vec, int commit, const float *__restrict__ logits,
+            const float *__restrict__ q, const float *__restrict__ row_m, const double *__restrict__ row_z,
+            const int32_t *__restrict__ sel_row, const int32_t *__restrict__ sel_mode, const double *__restrict__ mass,
+            const float *__restrict__ v, const int32_t *__restrict__ stream_ids, const int32_t *__restrict__ alen,
+            int32_t *__restrict__ ytok, int32_t *kv_len, int32_t *pred_next) {
+    __shared__ double part[SS_THREADS];
+    __shared__ double s_base, s_target;
+    __shared__ int s_chunk, s_first, s_last;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int rs = sel_row[b], mode = sel_mode[b];
+    if (mode != 0) {   // the whole block takes the same side
+        if (tid == 0) {
+            double total = 0.0;
+            for (int c = 0; c < C; ++c) total += mass[(size_t)b * C + c];
+            const double target = (double)v[b] * total;
+            double cum = 0.0, base = 0.0;
+            int chunk = -1, last_pos = 0;
+            double last_base = 0.0;
+            for (int c = 0; c < C; ++c) {
+                const double mc = mass[(size_t)b * C + c];
+                if (mc > 0.0) { last_pos = c; last_base = cum; }
+                if (chunk < 0 && cum + mc > target) { chunk = c; base = cum; }
+                cum += mc;
+            }
+            if (chunk < 0) { chunk = last_pos; base = last_base; }   // v * total rounded up to the total
+            s_chunk = chunk;
+            s_base = base;
+            s_target = target;
+            s_first = 0x7fffffff;
+            s_last = -1;
+        }
+        __syncthreads();
+        const int i0 = (s_chunk * SS_THREADS + tid) * SS_PER_THREAD;
+        float x[8], qv[8];
+        ss_load8(logits + (size_t)rs * V, i0, V, vec, -INFINITY, x);
+        ss_load8(q + (size_t)min(rs + 1, rows - 1) * V, i0, V, vec, 0.f, qv);
+        const float M = row_m[rs];
+        const double Z = row_z[rs];
+        double w[8], ts = 0.0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { w[e] = ss_weight(x[e], qv[e], M, Z, mode == 1); ts += w[e]; }
+        part[tid] = ts;
+        __syncthreads();
+        double cum = s_base;
+        for (int t = 0; t < tid; ++t) cum += part[t];   // left to right: thread t + 1 starts where thread t ends
+        const double target = s_target;
+        int first = 0x7fffffff, last = -1;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            cum += w[e];
+            if (w[e] > 0.0) {
+                last = i0 + e;
+                if (cum > target) first = min(first, i0 + e);
+            }
+        }
+        if (first != 0x7fffffff) atomicMin(&s_first, first);
+        if (last >= 0) atomicMax(&s_last, last);
+        __syncthreads();
+        if (tid == 0) ytok[b] = s_first != 0x7fffffff ? s_first : max(s_last, 0);
+    }
+    if (commit && tid == 0) {
+        const int slot = min(max(stream_ids[b], 0), max_batch - 1);
+        kv_len[slot] += alen[b];
+        pred_next[slot] = ytok[b];   // written by this thread or by the accept kernel
+    }
+}
+
+size_t ss_workspace_bytes(int rows, int vocab, int batch) {
+    const size_t C = (vocab + SS_THREADS * SS_PER_THREAD - 1) / (SS_THREADS * SS_PER_THREAD);
+    return (size_t)rows * C * 8 + (size_t)rows * 16 + (size_t)batch * 8 + (size_t)batch * C * 8 + 64;
+}
+
+void launch_ss(Ctx *c, const SsArgs &a) {
+    const int rows = a.batch * a.k, V = a.vocab;
+    const int C = (V + SS_THREADS * SS_PER_THREAD - 1) / (SS_THREADS * SS_PER_THREAD);
+    const bool vec = (V & 3) == 0 && V >= 4 && ((uintptr_t)a.logits & 15) == 0 && ((uintptr_t)a.draft_probs & 15) == 0;
+    // carve the workspace: doubles first
+    char *p = (char *)c->ss_ws;
+    double *row_z = (double *)p;  p += (size_t)rows * 8;
+    double *mass = (double *)p;   p += (size_t)a.batch * C * 8;
+    float *pm = (float *)p;       p += (size_t)rows * C * 4;
+    float *pz = (float *)p;       p += (size_t)rows * C * 4;
+    float *row_m = (float *)p;    p += (size_t)rows * 4;
+    int32_t *sel_row = (int32_t *)p;  p += (size_t)a.batch * 4;
+    int32_t *sel_mode = (int32_t *)p;
+    ProfScope ps(c, KC_SS);
+    hipLaunchKernelGGL(k_ss_stats, dim3(C, rows), dim3(SS_THREADS), 0, c->stream, a.logits, V, C, vec, pm, pz);
+    hipLaunchKernelGGL(k_ss_accept, dim3(a.batch), dim3(64), 0, c->stream, a.k, V, C, c->cfg.max_batch, a.logits, pm, pz,
+                       a.stream_ids, c->d_pred_next, a.pending_tokens, a.tokens, a.draft_probs, a.u_accept, row_m, row_z,
+                       sel_row, sel_mode, a.accepted_len, a.emitted_token, a.alpha);
+    hipLaunchKernelGGL(k_ss_mass, dim3(C, a.batch), dim3(SS_THREADS), 0, c->stream, V, C, rows, vec, a.logits, a.draft_probs,
+                       row_m, row_z, sel_row, sel_mode, mass);
+    hipLaunchKernelGGL(k_ss_sample, dim3(a.batch), dim3(SS_THREADS), 0, c->stream, V, C, rows, c->cfg.max_batch, vec,
+                       a.commit ? 1 : 0, a.logits, a.draft_probs, row_m, row_z, sel_row, sel_mode, mass, a.u_sample,
+                       a.stream_ids, a.accepted_len, a.emitted_token, c->d_kv_len, c->d_pred_next);
+}
+
+}  // namespace wisv

@@ -160,6 +160,8 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     c->ev_round[0] = c->ev_round[1] = nullptr;
     c->logits = nullptr;
     c->logits_rows = 0;
+    c->ss_ws = nullptr;
+    c->d_ss_q = c->d_ss_u = c->d_ss_v = nullptr;
     c->last_rows = 0;
     memset(c->prof_ms, 0, sizeof c->prof_ms);
     memset(c->prof_n, 0, sizeof c->prof_n);
@@ -349,6 +351,14 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     }
     CREATE_TRY(dalloc(c, &c->logits, (size_t)R * V));
     c->logits_rows = R;
+    {
+        char *p;
+        CREATE_TRY(dalloc(c, &p, ss_workspace_bytes(R, V, g.max_batch)));
+        c->ss_ws = p;
+    }
+    CREATE_TRY(dalloc(c, &c->d_ss_u, R));
+    CREATE_TRY(dalloc(c, &c->d_ss_v, g.max_batch));
+    c->d_ss_q = nullptr;
     CREATE_TRY(hipStreamSynchronize(c->stream));
 #undef CREATE_TRY
     *out = c;
@@ -617,6 +627,143 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
     return WISV_OK;
 }
 
+// ------------------------------------------------------------------------------------------ speculative sampling
+
+extern "C" int wisv_ss_verify_round(wisv_ctx *ctx, const wisv_ss_in *in, wisv_ss_out *out) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (!in || !out) return fail(c, WISV_EINVAL, "ss_in / ss_out is NULL");
+    const wisv_config &g = c->cfg;
+    if (in->batch < 1 || in->batch > g.max_batch) return fail(c, WISV_EINVAL, "batch %d outside [1, %d]", in->batch, g.max_batch);
+    if (in->k < 1 || in->k > g.max_k) return fail(c, WISV_EINVAL, "k %d outside [1, max_k = %d]", in->k, g.max_k);
+    if (!in->stream_ids || !in->draft_tokens || !in->draft_probs || !in->u_accept || !in->u_sample)
+        return fail(c, WISV_EINVAL, "a required ss_in pointer is NULL");
+    if (!out->accepted_len || !out->correction_token || !out->alpha) return fail(c, WISV_EINVAL, "a required ss_out pointer is NULL");
+    if (in->flags & ~(WISV_FLAG_NO_COMMIT | WISV_FLAG_DEVICE_IO)) return fail(c, WISV_EINVAL, "unknown flag bits 0x%x", in->flags);
+    const int B = in->batch, K = in->k, R = B * K, V = g.vocab;
+    const bool dev_io = in->flags & WISV_FLAG_DEVICE_IO, commit = !(in->flags & WISV_FLAG_NO_COMMIT);
+
+    int len_ub = 0;
+    if (!dev_io) {
+        std::vector<char> seen(g.max_batch, 0);
+        for (int b = 0; b < B; ++b) {
+            const int s = in->stream_ids[b];
+            if (s < 0 || s >= g.max_batch) return fail(c, WISV_EINVAL, "stream_ids[%d] = %d outside [0, %d)", b, s, g.max_batch);
+            if (seen[s]) return fail(c, WISV_EINVAL, "stream id %d appears twice", s);
+            seen[s] = 1;
+            if (c->h_len_ub[s] + K > g.max_ctx)
+                return fail(c, WISV_ESTATE, "stream %d: cached length %d + k %d exceeds max_ctx %d", s, c->h_len_ub[s], K, g.max_ctx);
+            len_ub = std::max(len_ub, c->h_len_ub[s] + K);
+            if (!(in->u_sample[b] >= 0.f && in->u_sample[b] < 1.f)) return fail(c, WISV_EINVAL, "u_sample[%d] outside [0, 1)", b);
+        }
+        for (int m = 0; m < R; ++m) {
+            if (in->draft_tokens[m] < 0 || in->draft_tokens[m] >= V)
+                return fail(c, WISV_EINVAL, "draft_tokens[%d] = %d outside the vocabulary", m, in->draft_tokens[m]);
+            if (!(in->u_accept[m] >= 0.f && in->u_accept[m] < 1.f)) return fail(c, WISV_EINVAL, "u_accept[%d] outside [0, 1)", m);
+        }
+    } else {
+        for (int s = 0; s < g.max_batch; ++s) len_ub = std::max(len_ub, c->h_len_ub[s] + K);
+        if (len_ub > g.max_ctx) return fail(c, WISV_ESTATE, "a stream may exceed max_ctx; resynchronise with wisv_get_state");
+    }
+    c->pending_valid = false;
+
+    HIP_TRY(c, hipSetDevice(g.device_id));
+    SsArgs a;
+    a.batch = B;
+    a.k = K;
+    a.vocab = V;
+    a.logits = c->logits;
+    a.pending_tokens = nullptr;
+    a.commit = commit;
+    if (!dev_io) {
+        if (!c->d_ss_q) HIP_TRY(c, dalloc(c, &c->d_ss_q, (size_t)c->rows_max * V));
+        HIP_TRY(c, hipMemcpyAsync(c->d_stream_ids, in->stream_ids, B * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_tokens, in->draft_tokens, R * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_ss_q, in->draft_probs, (size_t)R * V * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_ss_u, in->u_accept, R * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_ss_v, in->u_sample, B * 4, hipMemcpyHostToDevice, c->stream));
+        a.stream_ids = c->d_stream_ids;
+        a.tokens = c->d_tokens;
+        a.draft_probs = c->d_ss_q;
+        a.u_accept = c->d_ss_u;
+        a.u_sample = c->d_ss_v;
+        a.accepted_len = c->d_alen;
+        a.emitted_token = c->d_ytok;
+        a.alpha = c->d_pacc;
+    } else {
+        a.stream_ids = in->stream_ids;
+        a.tokens = in->draft_tokens;
+        a.draft_probs = in->draft_probs;
+        a.u_accept = in->u_accept;
+        a.u_sample = in->u_sample;
+        a.accepted_len = out->accepted_len;
+        a.emitted_token = out->correction_token;
+        a.alpha = out->alpha;
+    }
+    Fwd f;
+    f.rows = R;
+    f.batch = B;
+    f.k = K;
+    f.stream_ids = a.stream_ids;
+    f.tokens = a.tokens;
+    f.keep_logits = true;
+    f.max_len_ub = len_ub;
+
+    HIP_TRY(c, hipEventRecord(c->ev_round[0], c->stream));
+    { ProfScope empty(c, KC_EMPTY); }
+    enqueue_forward(c, f);
+    launch_ss(c, a);
+    HIP_TRY(c, hipEventRecord(c->ev_round[1], c->stream));
+    HIP_TRY(c, hipGetLastError());
+    c->last_rows = R;
+
+    if (!dev_io) {
+        HIP_TRY(c, hipMemcpyAsync(out->accepted_len, c->d_alen, B * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(out->correction_token, c->d_ytok, B * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(out->alpha, c->d_pacc, R * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        if (commit)
+            for (int b = 0; b < B; ++b) c->h_len_ub[in->stream_ids[b]] += out->accepted_len[b];
+    } else if (commit) {
+        for (int s = 0; s < g.max_batch; ++s) c->h_len_ub[s] = std::min(c->h_len_ub[s] + K, g.max_ctx);
+    }
+    return WISV_OK;
+}
+
+extern "C" int wisv_ss_decide(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab, const float *logits,
+                              const int32_t *pending_tokens, const int32_t *draft_tokens, const float *draft_probs,
+                              const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *emitted_token,
+                              float *alpha) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    const wisv_config &g = c->cfg;
+    if (batch < 1 || batch > g.max_batch) return fail(c, WISV_EINVAL, "batch %d outside [1, %d]", batch, g.max_batch);
+    if (k < 1 || k > g.max_k) return fail(c, WISV_EINVAL, "k %d outside [1, max_k = %d]", k, g.max_k);
+    if (vocab < 1 || vocab > g.vocab) return fail(c, WISV_EINVAL, "vocab %d outside [1, %d] (the scratch is sized for the ctx's vocabulary)", vocab, g.vocab);
+    if (!logits || !pending_tokens || !draft_tokens || !draft_probs || !u_accept || !u_sample || !accepted_len ||
+        !emitted_token || !alpha)
+        return fail(c, WISV_EINVAL, "a pointer argument is NULL");
+    HIP_TRY(c, hipSetDevice(g.device_id));
+    SsArgs a;
+    a.batch = batch;
+    a.k = k;
+    a.vocab = vocab;
+    a.logits = logits;
+    a.stream_ids = nullptr;
+    a.pending_tokens = pending_tokens;
+    a.tokens = draft_tokens;
+    a.draft_probs = draft_probs;
+    a.u_accept = u_accept;
+    a.u_sample = u_sample;
+    a.accepted_len = accepted_len;
+    a.emitted_token = emitted_token;
+    a.alpha = alpha;
+    a.commit = false;
+    launch_ss(c, a);
+    HIP_TRY(c, hipGetLastError());
+    return WISV_OK;
+}
+
 // ------------------------------------------------------------------------------------------ state helpers
 
 static int check_slot(Ctx *c, int32_t s) {
@@ -780,7 +927,7 @@ extern "C" int wisv_calibration_copy(wisv_ctx *ctx, void *dst, const void *src, 
 }
 
 static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm_qkv_o_down", "gemm_gate_up", "rope_append", "attention", "attention_combine",
-                                            "swiglu", "lm_head", "argmax", "head", "decide", "event_pair_overhead"};
+                                            "swiglu", "lm_head", "argmax", "head", "decide", "spec_sampling", "event_pair_overhead"};
 
 extern "C" int wisv_profile_enable(wisv_ctx *ctx, int32_t on) {
     if (!ctx) return WISV_EINVAL;

@@ -74,7 +74,7 @@ __device__ __forceinline__ void act_store4(const ActBuf &a, size_t i, float v0, 
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
 enum KernelClass {
     KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_LMHEAD,
-    KC_ARGMAX, KC_HEAD, KC_DECIDE, KC_EMPTY, KC_COUNT
+    KC_ARGMAX, KC_HEAD, KC_DECIDE, KC_SS, KC_EMPTY, KC_COUNT
 };
 
 // ---------------------------------------------------------------- the context
@@ -137,6 +137,8 @@ struct Ctx {
     float *att_o, *att_m, *att_l; // split-KV attention partials: [split][rows][heads][head_dim], [split][rows][heads]
     int att_max_splits;
     size_t logits_rows;
+    void *ss_ws;                  // speculative-sampling scratch: chunk statistics, normalisers, chunk weights
+    float *d_ss_q, *d_ss_u, *d_ss_v;   // its host-mode input staging (d_ss_q is allocated by the first call that needs it)
 
     // timing
     hipEvent_t ev_round[2];
@@ -182,6 +184,22 @@ void launch_set_pred_next(Ctx *c, int slot, int row, int new_len);
 // ---------------------------------------------------------------- decision head + scan (kernels_head.hip)
 void launch_head_decide(Ctx *c, const Fwd &f, const wisv_round_in &in_dev, const wisv_round_out &out_dev);
 void launch_pad_cols(Ctx *c, const void *src, void *dst, int rows, int cols, int cols_pad);
+
+// ---------------------------------------------------------------- speculative-sampling decision (kernels_ss.hip)
+struct SsArgs {                    // all device pointers
+    int batch, k, vocab;
+    const float *logits;           // [batch*k][vocab]
+    const int32_t *stream_ids;     // [batch]; pending token = pred_next of the slot (used when pending_tokens is null)
+    const int32_t *pending_tokens; // [batch] or null
+    const int32_t *tokens;         // [batch*k]
+    const float *draft_probs;      // [batch*k][vocab]
+    const float *u_accept, *u_sample;
+    int32_t *accepted_len, *emitted_token;
+    float *alpha;
+    bool commit;                   // kv_len += A, pred_next = emitted token (needs stream_ids)
+};
+size_t ss_workspace_bytes(int rows, int vocab, int batch);
+void launch_ss(Ctx *c, const SsArgs &a);
 
 // ---------------------------------------------------------------- weight-streaming GEMM (kernels_gemm.hip)
 constexpr int MAX_SPLITS = 16;

@@ -8,6 +8,7 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 import torch
 
+from oracle import spec_sampling as ss
 from oracle import wisv_oracle as wo
 from paper_2604_17701_amd import binding
 from wisv_inputs import configs, gen
@@ -155,3 +156,33 @@ def check_invariants(gpu: Dict[str, np.ndarray], drafts: np.ndarray, k: int):
             assert y[b] != drafts[b, a[b]]
         p = gpu["p_accept"][b]
         assert np.all((p >= 0) & (p <= 1))
+
+
+# ---- speculative sampling (Sec. II-A) -----------------------------------------------------------
+
+def check_ss_stream(logits, pending, tokens, q, u, v, got_a, got_tok, got_alpha, tol, stats):
+    """One stream against the oracle; logits are the oracle side's (float32 inputs or its own forward)."""
+    k = len(tokens)
+    a, tok, alpha = ss.verify_block(logits, pending, tokens, q, u, v)
+    np.testing.assert_allclose(got_alpha, alpha, rtol=tol, atol=tol * 1e-3)
+    stats["alpha_err"] = max(stats.get("alpha_err", 0.0), float(np.max(np.abs(got_alpha - alpha) / np.maximum(alpha, 1e-30))))
+    decisive = all(abs(float(u[j]) - alpha[j]) > tol * max(alpha[j], 1e-30) for j in range(min(a + 1, k)))
+    stats["streams"] = stats.get("streams", 0) + 1
+    if not decisive:
+        stats["a_inside_margin"] = stats.get("a_inside_margin", 0) + 1
+        # the first position whose decision a rounding error could turn bounds what is valid
+        first_soft = min(j for j in range(min(a + 1, k)) if abs(float(u[j]) - alpha[j]) <= tol * max(alpha[j], 1e-30))
+        assert first_soft <= got_a <= k
+        return
+    assert got_a == a, (got_a, a, alpha, u)
+    if a == 0:
+        assert got_tok == pending
+        return
+    w = ss.residual(ss.softmax(logits[a - 1]), q[a]) if a < k else ss.softmax(logits[k - 1])
+    c = np.cumsum(w)
+    target = float(v) * c[-1]
+    assert w[got_tok] > 0.0, "a token of zero weight was emitted"
+    lo = c[got_tok - 1] if got_tok else 0.0
+    assert lo - tol * c[-1] <= target <= c[got_tok] + tol * c[-1], (got_tok, tok, lo, c[got_tok], target)
+    stats["tokens"] = stats.get("tokens", 0) + 1
+    stats["tokens_equal"] = stats.get("tokens_equal", 0) + int(got_tok == tok)

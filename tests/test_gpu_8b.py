@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity import OracleSide, TOL_BF16, check_invariants, compare_stream, row_rel_err, to_host_weights
+from parity import OracleSide, TOL_BF16, check_invariants, check_ss_stream as check_stream, compare_stream, row_rel_err, to_host_weights
 from paper_2604_17701_amd import binding
 from wisv_inputs import configs, gen
 from wisv_inputs.configs import PROTO_FH, PROTO_SH
@@ -122,3 +122,51 @@ def test_config3_batch16_ctx2048_k6_tau_sweep(target8b):
 
 def test_config4_batch64_ctx8192_k8_mixed_protocols(target8b):
     _run(configs.get(4), target8b, sampled=[5, 38])     # one SH (odd) and one FH (even) stream
+
+
+def test_config1_shape_speculative_sampling_round(target8b):
+    """The stochastic verifier of Sec. II-A at the 8B shape (two streams, L = 512, K = 4): alpha, A and the
+    emitted token against the oracle's forward + rule.  The two forwards differ by the bf16 path's rounding
+    (logits to about 1e-4 relative), so the margin inside which an integer may differ is 3e-4 (measured alpha error: 7e-5)."""
+    from oracle import spec_sampling as ss
+    wd, wh = target8b
+    w1 = configs.get(1)
+    w = configs.Workload("ss_8b_b2_l512_k4", 1, w1.model, batch=2, ctx=512, k=4, protos=(PROTO_FH,) * 2)
+    m, k, batch = w.model, w.k, w.batch
+    kv = binding.new_kv_cache(m, batch, w.ctx + k, DEV)
+    ctx = binding.Context(m, wd, batch, w.ctx + k, k, kv_cache=kv)
+    side = OracleSide(w, wh)
+    pending = []
+    for b in range(batch):
+        for l in range(m.n_layers):
+            kk, vv = gen.synthetic_kv(w, b, l, DEV)
+            binding.kv_fill(kv, m, l, b, kk, vv)
+        side.load_synthetic_kv(b, DEV)
+        pending.append(gen.synthetic_pred_next(w, b))
+        ctx.wisv_set_state(b, w.ctx, pending[b])
+    tokens = gen.randint(77, "ss_tok", (batch, k), m.vocab).numpy().astype(np.int32)
+    tokens[:, 0] = pending
+    olog = []
+    for b in range(batch):
+        for j in range(1, k):                               # drafts follow the oracle's greedy chain except the last of stream 1
+            if not (b == 1 and j == k - 1):
+                tokens[b, j] = side.next_token_fn(b)([int(t) for t in tokens[b, :j]])
+        olog.append(side.orc.forward_block(side.cache[b], w.ctx, tokens[b], want_logits=True)["logits"])
+    # drafter mass on the drafted token around the target's own probability of it, so that alpha lands on both sides of 1
+    p_tok = np.array([[1.0] + [float(ss.softmax(olog[b][j - 1])[tokens[b, j]]) for j in range(1, k)] for b in range(batch)])
+    mass = np.clip(p_tok * np.array([[1.0, 0.5, 3.0, 1.5], [1.0, 4.0, 0.8, 2.0]]), 0.0, 0.9)
+    q = gen.draft_distributions(77, batch * k, m.vocab, tokens.reshape(-1), mass.reshape(-1)).reshape(batch, k, -1)
+    v = gen.unit_uniforms(77, "ss_v", batch)
+    stats = {}
+    for trial, uscale in enumerate((0.2, 0.6, 1.0)):
+        u = gen.unit_uniforms(77 + trial, "ss_u", batch * k).reshape(batch, k) * np.float32(uscale)
+        g = ctx.wisv_ss_verify_round(np.arange(batch), tokens, q, u, v, k, binding.WISV_FLAG_NO_COMMIT)
+        for b in range(batch):
+            check_stream(olog[b], pending[b], tokens[b], q[b], u[b], float(v[b]), int(g["accepted_len"][b]),
+                         int(g["correction_token"][b]), g["alpha"][b], 3e-4, stats)
+        stats[f"A@{uscale}"] = g["accepted_len"].tolist()
+    print(f"\n[{w.name}] {stats}", flush=True)
+    assert stats.get("a_inside_margin", 0) <= 1
+    ctx.wisv_destroy()
+    del kv
+    torch.cuda.empty_cache()

@@ -264,3 +264,32 @@ def pack_hidden(w: Workload, hd_by_stream: Sequence[torch.Tensor],
     else:
         hd = torch.zeros((0, w.model.d_draft), dtype=torch_dtype(w.model))
     return hd, row_map
+
+
+# --------------------------------------------------------------------------- speculative-sampling inputs
+
+def unit_uniforms(seed: int, tag: str, n: int) -> np.ndarray:
+    """n float32 values in [0, 1): the uniform numbers a stochastic verifier consumes (inputs on both sides)."""
+    u = uniform01(seed, tag, n).astype(np.float32)
+    return np.minimum(u, np.float32(1.0) - np.float32(2.0 ** -24))
+
+
+def target_logits(seed: int, rows: int, vocab: int, scale: float) -> np.ndarray:
+    """Stand-in target logits [rows, vocab]: N(0, scale^2); a scale of 3-4 gives the peaked next-token
+    distributions of a trained decoder, a scale below 1 the flat ones of a random-weight target."""
+    return normal(seed, "ss_logits", (rows, vocab), scale, torch.float32).numpy()
+
+
+def draft_distributions(seed: int, rows: int, vocab: int, tokens: np.ndarray, token_mass: np.ndarray,
+                        zero_frac: float = 0.25) -> np.ndarray:
+    """Stand-in drafter distributions [rows, vocab] (float32, each row sums to 1 up to rounding): log-normal
+    weights, a share zero_frac of the entries exactly zero (a truncated drafter), normalised to 1 - token_mass[r],
+    plus token_mass[r] on the drafted token tokens[r]."""
+    w = torch.exp(normal(seed, "ss_q", (rows, vocab), 1.5, torch.float32).double())
+    keep = randint(seed, "ss_q_zero", (rows, vocab), 1 << 16) >= int(zero_frac * (1 << 16))
+    w = (w * keep).numpy()
+    w[:, 0] += 1e-3                                     # no row is empty
+    mass = np.asarray(token_mass, dtype=np.float64).reshape(rows, 1)
+    q = w / w.sum(axis=1, keepdims=True) * (1.0 - mass)
+    q[np.arange(rows), np.asarray(tokens).reshape(rows)] += mass[:, 0]
+    return q.astype(np.float32)
