@@ -6,7 +6,10 @@ KV cache, decision head, first-reject scan) on synthetic inputs already resident
 Prints ONE JSON line: verified draft tokens/s and ms per round, the roofline of the dominant kernel
 (HIP-event durations measured here), and the CPU oracle timed on the host cores as a baseline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline] [--verifier wisv|ss]
+
+--verifier ss times the speculative-sampling verifier (Sec. II-A) on the same forward instead of the decision
+head: same workload, synthetic drafter distributions and uniform numbers resident in HBM.
 """
 from __future__ import annotations
 
@@ -141,6 +144,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default: the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verifier", choices=("wisv", "ss"), default="wisv",
+                    help="wisv: CSI-aware decision head (the headline path); ss: speculative sampling on the same forward")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="also run N plain 1 GiB copy kernels (known traffic, for scaling rocprofv3 memory counters)")
     a = ap.parse_args()
@@ -165,6 +170,12 @@ def main():
     kv = binding.new_kv_cache(m, w.batch, max_ctx, dev)
     ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
     rnd, inputs = build_round(ctx, w, binding, gen, np, torch)
+    if a.verifier == "ss":
+        # same drafts; drafter distributions with a small mass on the drafted token, uniform numbers as inputs
+        q = torch.from_numpy(gen.draft_distributions(w.seed, w.m, m.vocab, inputs["drafts"].reshape(-1), np.full(w.m, 2e-5)))
+        rnd = ctx.ss_device_round(np.arange(w.batch), inputs["drafts"], q, gen.unit_uniforms(w.seed, "ss_u", w.m),
+                                  gen.unit_uniforms(w.seed, "ss_v", w.batch), w.k, binding.WISV_FLAG_NO_COMMIT)
+        del q
     log(f"{w.name}: inputs resident after {time.time() - t0:.1f}s")
 
     # ---- the timed region: exactly `steps` rounds between two synchronisations
@@ -243,10 +254,18 @@ def main():
         "committed_tokens_per_s": float((res["accepted_len"] + 1).sum()) / (ms * 1e-3),
         "mean_accepted_len": float(res["accepted_len"].mean()),
         "gemm_mfma": gemm_mfma,
-        "link_model": link_model_rows(w, ms * 1e-3, res),
+        "link_model": link_model_rows(w, ms * 1e-3, res) if a.verifier == "wisv" else None,
         "kernels": kernels,
     }
-    if not a.no_cpu_baseline:
+    if a.verifier == "ss":
+        # the four decision kernels are bracketed by one event pair; they must read every logits row once and, for
+        # one row per stream, the logits and the drafter's distribution once more
+        ss_bytes = (w.m + 2 * w.batch) * m.vocab * 4
+        out["config"]["verifier"] = "speculative sampling (Sec. II-A)"
+        out["spec_sampling"] = {"us_per_round": kernels["spec_sampling"]["avg_us"], "algorithmic_bytes": ss_bytes,
+                                "achieved_GBs": ss_bytes / (kernels["spec_sampling"]["avg_us"] * 1e-6) / 1e9,
+                                "logits_written_by_lm_head_bytes": w.m * m.vocab * 4}
+    if not a.no_cpu_baseline and a.verifier == "wisv":
         t2 = time.time()
         out["cpu_baseline"] = cpu_baseline(w, wd, inputs, gen, np, torch)
         log(f"cpu baseline took {time.time() - t2:.1f}s")

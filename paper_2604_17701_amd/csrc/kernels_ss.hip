@@ -24,6 +24,29 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
     return v;
 }
 
+// exclusive prefix sum over the block's 256 threads (wave scans, then the wave totals left to right) and the block total
+__device__ __forceinline__ double block_scan_excl(double v, double *wave_tot, double &total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    double inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    const double below = __shfl_up(inc, 1, 64);
+    if (lane == 63) wave_tot[w] = inc;
+    __syncthreads();
+    double off = 0.0, tot = 0.0;
+#pragma unroll
+    for (int i = 0; i < SS_THREADS / 64; ++i) {
+        if (i < w) off += wave_tot[i];
+        tot += wave_tot[i];
+    }
+    total = tot;
+    __syncthreads();
+    return off + (lane ? below : 0.0);
+}
+
 // eight consecutive elements of a row starting at i0 (a multiple of 8); elements at or beyond n read as `fill`.
 // Every lane issues the same loads (clamped addresses), the selection comes afterwards.
 __device__ __forceinline__ void ss_load8(const float *__restrict__ row, int i0, int n, bool vec, float fill, float x[8]) {
@@ -68,43 +91,45 @@ k_ss_stats(const float *__restrict__ logits, int V, int C, bool vec, float *__re
     }
 }
 
-// one wave per stream; lane j handles position j, lanes 1..k also the normaliser of logits row j - 1
-__global__ void __launch_bounds__(64)
+// one block per stream, one wave per logits row of the stream: wave w reduces the chunk statistics of row w and
+// decides position w + 1 (wave 0 also position 0)
+__global__ void __launch_bounds__(1024)
 k_ss_accept(int k, int V, int C, int max_batch, const float *__restrict__ logits, const float *__restrict__ pm,
             const float *__restrict__ pz, const int32_t *__restrict__ stream_ids, const int32_t *__restrict__ pred_next,
             const int32_t *__restrict__ pending_tokens, const int32_t *__restrict__ tokens, const float *__restrict__ q,
             const float *__restrict__ u, float *__restrict__ row_m, double *__restrict__ row_z, int32_t *__restrict__ sel_row,
             int32_t *__restrict__ sel_mode, int32_t *__restrict__ alen, int32_t *__restrict__ ytok, float *__restrict__ alpha_out) {
-    const int b = blockIdx.x, j = threadIdx.x;
+    __shared__ int s_reject[WISV_MAX_K];
+    const int b = blockIdx.x, w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rp = b * k + w;
     const int pending = pending_tokens ? pending_tokens[b] : pred_next[min(max(stream_ids[b], 0), max_batch - 1)];
-    bool reject = false;
-    if (j <= k) {
-        double alpha;
-        if (j == 0) {
-            alpha = tokens[b * k] == pending ? 1.0 : 0.0;
-        } else {
-            const int rp = b * k + j - 1;
-            float M = -INFINITY;
-            for (int c = 0; c < C; ++c) M = fmaxf(M, pm[(size_t)rp * C + c]);
-            double Z = 0.0;
-            for (int c = 0; c < C; ++c) Z += (double)pz[(size_t)rp * C + c] * (double)expf(pm[(size_t)rp * C + c] - M);
-            row_m[rp] = M;
-            row_z[rp] = Z;
-            alpha = 1.0;
-            if (j < k) {
-                const int t = min(max(tokens[rp + 1], 0), V - 1);
-                const double P = (double)expf(logits[(size_t)rp * V + t] - M) / Z, qv = (double)q[(size_t)(rp + 1) * V + t];
-                alpha = qv <= P ? 1.0 : P / qv;
-            }
+    float M = -INFINITY;
+    for (int c = lane; c < C; c += 64) M = fmaxf(M, pm[(size_t)rp * C + c]);
+    M = wave_max(M);
+    double Z = 0.0;
+    for (int c = lane; c < C; c += 64) Z += (double)pz[(size_t)rp * C + c] * (double)expf(pm[(size_t)rp * C + c] - M);
+    Z = wave_sum_f64(Z);
+    if (lane == 0) {
+        row_m[rp] = M;
+        row_z[rp] = Z;
+        if (w + 1 < k) {
+            const int t = min(max(tokens[rp + 1], 0), V - 1);
+            const double P = (double)expf(logits[(size_t)rp * V + t] - M) / Z, qv = (double)q[(size_t)(rp + 1) * V + t];
+            const double alpha = qv <= P ? 1.0 : P / qv;
+            alpha_out[rp + 1] = (float)alpha;
+            s_reject[w + 1] = !((double)u[rp + 1] < alpha);
         }
-        if (j < k) {
-            alpha_out[b * k + j] = (float)alpha;
-            reject = !((double)u[b * k + j] < alpha);
+        if (w == 0) {
+            const double alpha = tokens[b * k] == pending ? 1.0 : 0.0;
+            alpha_out[b * k] = (float)alpha;
+            s_reject[0] = !((double)u[b * k] < alpha);
         }
     }
-    const unsigned long long rej = __ballot(reject);
-    if (j == 0) {
-        const int A = rej ? __builtin_ctzll(rej) : k;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int A = k;
+        for (int j = k - 1; j >= 0; --j)
+            if (s_reject[j]) A = j;
         alen[b] = A;
         sel_row[b] = b * k + max(A, 1) - 1;
         sel_mode[b] = A == 0 ? 0 : A < k ? 1 : 2;    // 0: emit the pending token; 1: residual of position A; 2: target after the block
@@ -146,34 +171,34 @@ k_ss_sample(int V, int C, int rows, int max_batch, bool vec, int commit, const f
             const int32_t *__restrict__ sel_row, const int32_t *__restrict__ sel_mode, const double *__restrict__ mass,
             const float *__restrict__ v, const int32_t *__restrict__ stream_ids, const int32_t *__restrict__ alen,
             int32_t *__restrict__ ytok, int32_t *kv_len, int32_t *pred_next) {
-    __shared__ double part[SS_THREADS];
-    __shared__ double s_base, s_target;
-    __shared__ int s_chunk, s_first, s_last;
+    extern __shared__ double s_chunks[];   // [C] chunk weights, then [C] their exclusive prefix sums
+    __shared__ double wave_tot[SS_THREADS / 64];
+    __shared__ int s_chunk, s_lastc, s_first, s_last;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int rs = sel_row[b], mode = sel_mode[b];
     if (mode != 0) {   // the whole block takes the same side
-        if (tid == 0) {
-            double total = 0.0;
-            for (int c = 0; c < C; ++c) total += mass[(size_t)b * C + c];
-            const double target = (double)v[b] * total;
-            double cum = 0.0, base = 0.0;
-            int chunk = -1, last_pos = 0;
-            double last_base = 0.0;
-            for (int c = 0; c < C; ++c) {
-                const double mc = mass[(size_t)b * C + c];
-                if (mc > 0.0) { last_pos = c; last_base = cum; }
-                if (chunk < 0 && cum + mc > target) { chunk = c; base = cum; }
-                cum += mc;
-            }
-            if (chunk < 0) { chunk = last_pos; base = last_base; }   // v * total rounded up to the total
-            s_chunk = chunk;
-            s_base = base;
-            s_target = target;
-            s_first = 0x7fffffff;
-            s_last = -1;
+        double *cw = s_chunks, *cex = s_chunks + C;
+        if (tid == 0) { s_chunk = 0x7fffffff; s_lastc = 0; s_first = 0x7fffffff; s_last = -1; }
+        double carry = 0.0;
+        for (int c0 = 0; c0 < C; c0 += SS_THREADS) {   // chunk weights and their exclusive prefix sums, 256 at a time
+            const int c = c0 + tid;
+            const double m = c < C ? mass[(size_t)b * C + c] : 0.0;
+            double tile_total;
+            const double ex = carry + block_scan_excl(m, wave_tot, tile_total);
+            if (c < C) { cw[c] = m; cex[c] = ex; }
+            carry += tile_total;
         }
+        const double target = (double)v[b] * carry;
         __syncthreads();
-        const int i0 = (s_chunk * SS_THREADS + tid) * SS_PER_THREAD;
+        for (int c = tid; c < C; c += SS_THREADS)
+            if (cw[c] > 0.0) {
+                atomicMax(&s_lastc, c);
+                if (cex[c] + cw[c] > target) atomicMin(&s_chunk, c);
+            }
+        __syncthreads();
+        const int chunk = s_chunk != 0x7fffffff ? s_chunk : s_lastc;   // else: v * total rounded up to the total
+        const double base = cex[chunk];
+        const int i0 = (chunk * SS_THREADS + tid) * SS_PER_THREAD;
         float x[8], qv[8];
         ss_load8(logits + (size_t)rs * V, i0, V, vec, -INFINITY, x);
         ss_load8(q + (size_t)min(rs + 1, rows - 1) * V, i0, V, vec, 0.f, qv);
@@ -182,11 +207,8 @@ k_ss_sample(int V, int C, int rows, int max_batch, bool vec, int commit, const f
         double w[8], ts = 0.0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) { w[e] = ss_weight(x[e], qv[e], M, Z, mode == 1); ts += w[e]; }
-        part[tid] = ts;
-        __syncthreads();
-        double cum = s_base;
-        for (int t = 0; t < tid; ++t) cum += part[t];   // left to right: thread t + 1 starts where thread t ends
-        const double target = s_target;
+        double chunk_total;
+        double cum = base + block_scan_excl(ts, wave_tot, chunk_total);
         int first = 0x7fffffff, last = -1;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -228,12 +250,12 @@ void launch_ss(Ctx *c, const SsArgs &a) {
     int32_t *sel_mode = (int32_t *)p;
     ProfScope ps(c, KC_SS);
     hipLaunchKernelGGL(k_ss_stats, dim3(C, rows), dim3(SS_THREADS), 0, c->stream, a.logits, V, C, vec, pm, pz);
-    hipLaunchKernelGGL(k_ss_accept, dim3(a.batch), dim3(64), 0, c->stream, a.k, V, C, c->cfg.max_batch, a.logits, pm, pz,
+    hipLaunchKernelGGL(k_ss_accept, dim3(a.batch), dim3(64 * a.k), 0, c->stream, a.k, V, C, c->cfg.max_batch, a.logits, pm, pz,
                        a.stream_ids, c->d_pred_next, a.pending_tokens, a.tokens, a.draft_probs, a.u_accept, row_m, row_z,
                        sel_row, sel_mode, a.accepted_len, a.emitted_token, a.alpha);
     hipLaunchKernelGGL(k_ss_mass, dim3(C, a.batch), dim3(SS_THREADS), 0, c->stream, V, C, rows, vec, a.logits, a.draft_probs,
                        row_m, row_z, sel_row, sel_mode, mass);
-    hipLaunchKernelGGL(k_ss_sample, dim3(a.batch), dim3(SS_THREADS), 0, c->stream, V, C, rows, c->cfg.max_batch, vec,
+    hipLaunchKernelGGL(k_ss_sample, dim3(a.batch), dim3(SS_THREADS), (size_t)C * 16, c->stream, V, C, rows, c->cfg.max_batch, vec,
                        a.commit ? 1 : 0, a.logits, a.draft_probs, row_m, row_z, sel_row, sel_mode, mass, a.u_sample,
                        a.stream_ids, a.accepted_len, a.emitted_token, c->d_kv_len, c->d_pred_next);
 }

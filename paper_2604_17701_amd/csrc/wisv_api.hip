@@ -641,6 +641,7 @@ extern "C" int wisv_ss_verify_round(wisv_ctx *ctx, const wisv_ss_in *in, wisv_ss
     if (!out->accepted_len || !out->correction_token || !out->alpha) return fail(c, WISV_EINVAL, "a required ss_out pointer is NULL");
     if (in->flags & ~(WISV_FLAG_NO_COMMIT | WISV_FLAG_DEVICE_IO)) return fail(c, WISV_EINVAL, "unknown flag bits 0x%x", in->flags);
     const int B = in->batch, K = in->k, R = B * K, V = g.vocab;
+    if (V > SS_MAX_VOCAB) return fail(c, WISV_EUNSUPPORTED, "vocabulary %d beyond what the sampling kernel serves (%d)", V, SS_MAX_VOCAB);
     const bool dev_io = in->flags & WISV_FLAG_DEVICE_IO, commit = !(in->flags & WISV_FLAG_NO_COMMIT);
 
     int len_ub = 0;
@@ -740,6 +741,7 @@ extern "C" int wisv_ss_decide(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t v
     if (batch < 1 || batch > g.max_batch) return fail(c, WISV_EINVAL, "batch %d outside [1, %d]", batch, g.max_batch);
     if (k < 1 || k > g.max_k) return fail(c, WISV_EINVAL, "k %d outside [1, max_k = %d]", k, g.max_k);
     if (vocab < 1 || vocab > g.vocab) return fail(c, WISV_EINVAL, "vocab %d outside [1, %d] (the scratch is sized for the ctx's vocabulary)", vocab, g.vocab);
+    if (vocab > SS_MAX_VOCAB) return fail(c, WISV_EUNSUPPORTED, "vocabulary %d beyond what the sampling kernel serves (%d)", vocab, SS_MAX_VOCAB);
     if (!logits || !pending_tokens || !draft_tokens || !draft_probs || !u_accept || !u_sample || !accepted_len ||
         !emitted_token || !alpha)
         return fail(c, WISV_EINVAL, "a pointer argument is NULL");

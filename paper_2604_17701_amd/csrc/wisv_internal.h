@@ -198,6 +198,7 @@ struct SsArgs {                    // all device pointers
     float *alpha;
     bool commit;                   // kv_len += A, pred_next = emitted token (needs stream_ids)
 };
+constexpr int SS_MAX_VOCAB = 4000 * 2048;   // the sampling kernel keeps one weight per 2048-token chunk in LDS
 size_t ss_workspace_bytes(int rows, int vocab, int batch);
 void launch_ss(Ctx *c, const SsArgs &a);
 
