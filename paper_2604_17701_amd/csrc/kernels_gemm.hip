@@ -662,8 +662,9 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     int s;
     int layout = MM_NORMAL;
     if (rows <= 16) {
-        // one row-block per wave: split k until about 4096 waves stream, a wave keeps at least 8 k-tiles
-        s = (4096 + g.nrb - 1) / g.nrb;
+        // one row-block per wave: split k until about 6144 waves stream (three workgroups per CU), a wave keeps
+        // at least 8 k-tiles
+        s = (6144 + g.nrb - 1) / g.nrb;
         s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 8))));
     } else {
         // about one workgroup per CU over (row-block groups) x (row tiles) x splits; a split keeps >= 8 k-tiles
@@ -690,7 +691,13 @@ bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf
     g.nrb = ws_padded_pair_blocks(features);
     g.kt_per_split = g.nkt;
     g.H = H;
-    if (rows <= 16) return launch_ws_t<1, 1, 8, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
+    if (rows <= 16) {
+        // no k-split here, so the workgroup count is fixed by the shape: seven waves per workgroup when that fills
+        // whole rounds of 256 CUs better than eight (14336 features: 256 workgroups instead of 224)
+        auto fill = [&](int wr) { const int wgs = (g.nrb + wr - 1) / wr; return (double)wgs / ((wgs + 255) / 256 * 256); };
+        if (fill(7) > fill(8)) return launch_ws_t<1, 1, 7, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
+        return launch_ws_t<1, 1, 8, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
+    }
     return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1));
 }
 
