@@ -695,8 +695,8 @@ bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf
         // no k-split here, so the workgroup count is fixed by the shape: seven waves per workgroup when that fills
         // whole rounds of 256 CUs better than eight (14336 features: 256 workgroups instead of 224)
         auto fill = [&](int wr) { const int wgs = (g.nrb + wr - 1) / wr; return (double)wgs / ((wgs + 255) / 256 * 256); };
-        if (fill(7) > fill(8)) return launch_ws_t<1, 1, 7, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
-        return launch_ws_t<1, 1, 8, 1, 8, EPI_SWIGLU>(c, g, 1, 36 * 1024);
+        if (fill(7) > fill(8)) return launch_ws_t<1, 1, 7, 1, 16, EPI_SWIGLU>(c, g, 1, 36 * 1024);
+        return launch_ws_t<1, 1, 8, 1, 16, EPI_SWIGLU>(c, g, 1, 36 * 1024);
     }
     return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1));
 }
@@ -712,7 +712,7 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     const int slots = rows <= 16 ? g.nrb : (g.nrb + MM_RB - 1) / MM_RB;
     {
         ProfScope ps(c, kclass);
-        const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 8, EPI_ARGMAX>(c, g, 1, 70 * 1024)
+        const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 16, EPI_ARGMAX>(c, g, 1, 70 * 1024)
                                    : launch_ws_many<EPI_ARGMAX>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1));
         if (!ok) return false;
     }
