@@ -92,8 +92,8 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         bf16_t *kw = a.kv_write + (size_t)slot * a.slot_stride + (size_t)g * a.ctx_pad * HD;
         bf16_t *vw = kw + (size_t)a.G * a.ctx_pad * HD;
         bf16_t *q16 = reinterpret_cast<bf16_t *>(qs);
-        for (int it = tid; it < (16 * NQ + 2 * a.K) * 64; it += 64 * NW) {
-            const int row = it >> 6, i = it & 63;
+        for (int it = tid; it < (16 * NQ + 2 * a.K) * 16; it += 64 * NW) {
+            const int row = it >> 4, i = (it & 15) * 4;   // features i .. i + 3 and their partners i + 64 .. i + 67
             int j, col;                      // token of the block, first column of the head in a qkv row
             if (row < 16 * NQ) {
                 const int rho = min(row, R - 1);
@@ -106,41 +106,61 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
                 j = row - 16 * NQ - a.K;
                 col = d_q + d_kv + g * HD;
             }
-            const float *src = a.qkv + (size_t)(m0 + j) * d_all + col;
+            const float *src = a.qkv + (size_t)(m0 + j) * d_all + col + i;
             // every slice is requested before the first is used (slices past the last re-read it and count as 0)
-            float xs[MAX_SPLITS], ys[MAX_SPLITS];
+            floatx4 xs[MAX_SPLITS], ys[MAX_SPLITS];
 #pragma unroll
             for (int p = 0; p < MAX_SPLITS; ++p) {
                 const size_t off = (size_t)min(p, a.n_partial - 1) * a.partial_stride;
-                xs[p] = src[off + i];
-                ys[p] = src[off + i + 64];
-            }
-            float x = xs[0], y = ys[0];
-#pragma unroll
-            for (int p = 1; p < MAX_SPLITS; ++p) {
-                x += p < a.n_partial ? xs[p] : 0.f;
-                y += p < a.n_partial ? ys[p] : 0.f;
+                xs[p] = *reinterpret_cast<const floatx4 *>(src + off);
+                ys[p] = *reinterpret_cast<const floatx4 *>(src + off + 64);
             }
             const int pos = min(L + j, a.max_ctx - 1);
-            const float co = a.cs[(size_t)pos * 64 + i], si = a.sn[(size_t)pos * 64 + i];
+            const floatx4 co = *reinterpret_cast<const floatx4 *>(a.cs + (size_t)pos * 64 + i);
+            const floatx4 si = *reinterpret_cast<const floatx4 *>(a.sn + (size_t)pos * 64 + i);
+            floatx4 x = xs[0], y = ys[0];
+#pragma unroll
+            for (int p = 1; p < MAX_SPLITS; ++p) {
+                const bool on = p < a.n_partial;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    x[c] += on ? xs[p][c] : 0.f;
+                    y[c] += on ? ys[p][c] : 0.f;
+                }
+            }
+            float r0[4], r1[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                r0[c] = x[c] * co[c] - y[c] * si[c];
+                r1[c] = y[c] * co[c] + x[c] * si[c];
+            }
             if (row < 16 * NQ) {
-                const float r0 = row < R ? x * co - y * si : 0.f, r1 = row < R ? y * co + x * si : 0.f;
                 // element (rho, dim) of operand (nq, t = dim / 32, plane): lane 16 ((dim % 32) / 8) + rho % 16, slot dim % 8
                 const int nq = row >> 4, bjq = row & 15;
-                bf16_t h0, l0, h1, l1;
-                split2(r0, h0, l0);
-                split2(r1, h1, l1);
                 const int e = i & 7, ln = 16 * ((i & 31) >> 3) + bjq, t0 = i >> 5;
-                q16[((((nq * 4 + t0) * 2 + 0) * 64 + ln) << 3) + e] = h0;
-                q16[((((nq * 4 + t0) * 2 + 1) * 64 + ln) << 3) + e] = l0;
-                q16[((((nq * 4 + t0 + 2) * 2 + 0) * 64 + ln) << 3) + e] = h1;
-                q16[((((nq * 4 + t0 + 2) * 2 + 1) * 64 + ln) << 3) + e] = l1;
+                bf16_t h0[4], l0[4], h1[4], l1[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    split2(row < R ? r0[c] : 0.f, h0[c], l0[c]);
+                    split2(row < R ? r1[c] : 0.f, h1[c], l1[c]);
+                }
+                auto pack = [](const bf16_t (&v)[4]) { return make_uint2(v[0] | ((unsigned)v[1] << 16), v[2] | ((unsigned)v[3] << 16)); };
+                *reinterpret_cast<uint2 *>(q16 + ((((nq * 4 + t0) * 2 + 0) * 64 + ln) << 3) + e) = pack(h0);
+                *reinterpret_cast<uint2 *>(q16 + ((((nq * 4 + t0) * 2 + 1) * 64 + ln) << 3) + e) = pack(l0);
+                *reinterpret_cast<uint2 *>(q16 + ((((nq * 4 + t0 + 2) * 2 + 0) * 64 + ln) << 3) + e) = pack(h1);
+                *reinterpret_cast<uint2 *>(q16 + ((((nq * 4 + t0 + 2) * 2 + 1) * 64 + ln) << 3) + e) = pack(l1);
             } else if (row < 16 * NQ + a.K) {
-                kw[(size_t)pos * HD + i] = f32_to_bf16(x * co - y * si);
-                kw[(size_t)pos * HD + i + 64] = f32_to_bf16(y * co + x * si);
+                bf16_t k0[4], k1[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) { k0[c] = f32_to_bf16(r0[c]); k1[c] = f32_to_bf16(r1[c]); }
+                *reinterpret_cast<uint2 *>(kw + (size_t)pos * HD + i) = make_uint2(k0[0] | ((unsigned)k0[1] << 16), k0[2] | ((unsigned)k0[3] << 16));
+                *reinterpret_cast<uint2 *>(kw + (size_t)pos * HD + i + 64) = make_uint2(k1[0] | ((unsigned)k1[1] << 16), k1[2] | ((unsigned)k1[3] << 16));
             } else {
-                vw[v_plane_index(pos, i, HD)] = f32_to_bf16(x);
-                vw[v_plane_index(pos, i + 64, HD)] = f32_to_bf16(y);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    vw[v_plane_index(pos, i + c, HD)] = f32_to_bf16(x[c]);
+                    vw[v_plane_index(pos, i + c + 64, HD)] = f32_to_bf16(y[c]);
+                }
             }
         }
         __syncthreads();   // the appended rows and the query operands are visible to the whole workgroup
