@@ -2,6 +2,7 @@
 
     python -m paper_2604_17701_amd.profile_summary kernels <kernel_stats.csv> <out.txt> "<command>"
     python -m paper_2604_17701_amd.profile_summary traffic <fetch counter_collection.csv> <write counter_collection.csv> <out.txt> "<commands>"
+    python -m paper_2604_17701_amd.profile_summary counters <counter_collection.csv> <out.txt> "<command>"
 
 The traffic summary scales FETCH_SIZE / WRITE_SIZE by what the same counters read for the library's plain
 1 GiB copy kernel in the same run, and records a hash of the kernel sources so that bench.py can tell whether
@@ -71,6 +72,35 @@ def traffic(fetch_csv: str, write_csv: str, out: str, command: str):
                         f"write_bytes_per_launch {wr.get(k, 0.0) * cw:12.0f}\n")
 
 
+def counters(csv_path: str, out: str, command: str):
+    """Per-kernel averages of whatever counters one --pmc run collected, plus the matrix-core figures they give:
+    executed bf16 MFMA flop per launch (SQ_INSTS_VALU_MFMA_MOPS_BF16 counts units of 512 flop) and the share of
+    the chip's SIMD cycles in which the MFMA unit was busy."""
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(csv_path)):
+        agg[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    names = sorted({c for k in agg.values() for c in k})
+    with open(out, "w") as f:
+        f.write("# per-launch averages of rocprofv3 --pmc counters (summed over the chip by the profiler)\n")
+        f.write(f"# command: {command}\n")
+        f.write(f"source_sha256 {source_hash()}\n")
+        for k in sorted(agg, key=lambda k: -sum(agg[k].get("SQ_BUSY_CU_CYCLES", agg[k][names[0]]))):
+            if not k.startswith("k_") or k in ("k_calibration_copy", "k_retile"):
+                continue
+            avg = {c: sum(v) / len(v) for c, v in agg[k].items()}
+            n = len(next(iter(agg[k].values())))
+            f.write(f"kernel {k}  launches {n}\n")
+            for c in names:
+                if c in avg:
+                    f.write(f"    {c:34s} {avg[c]:16.1f}\n")
+            if "SQ_INSTS_VALU_MFMA_MOPS_BF16" in avg:
+                f.write(f"    {'executed_bf16_mfma_flop':34s} {avg['SQ_INSTS_VALU_MFMA_MOPS_BF16'] * 512:16.4g}\n")
+            if avg.get("GRBM_GUI_ACTIVE") and "SQ_VALU_MFMA_BUSY_CYCLES" in avg:
+                # GRBM_GUI_ACTIVE comes summed over the 8 XCDs, the MFMA busy cycles over the 1024 SIMDs
+                share = avg["SQ_VALU_MFMA_BUSY_CYCLES"] / (avg["GRBM_GUI_ACTIVE"] / 8 * 1024)
+                f.write(f"    {'mfma_busy_share_of_simd_cycles':34s} {share:16.3f}\n")
+
+
 def read_traffic(path: str):
     """Parses a traffic summary: (source hash, {kernel: (launches, fetch bytes, write bytes per launch)})."""
     sha, table = None, {}
@@ -97,5 +127,7 @@ def template_args(kernel: str):
 if __name__ == "__main__":
     if sys.argv[1] == "kernels":
         kernels(*sys.argv[2:5])
+    elif sys.argv[1] == "counters":
+        counters(*sys.argv[2:5])
     else:
         traffic(*sys.argv[2:6])
