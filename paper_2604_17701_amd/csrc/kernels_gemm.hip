@@ -388,18 +388,22 @@ __device__ __forceinline__ void mm_epilogue(const GemmArgs &g, floatx16 (&acc)[R
     }
 }
 
-// NT: 32-row tiles per wave; NW waves, WM of them along the rows (NW / WM along the row-blocks); RP: pairs of row-blocks
-// per wave; KC: k-tiles per LDS chunk; U: register slots of the weight stream
-template <int NT, int WM, int NW, int RP, int KC, int U, int EPI>
+// NT: 32-row tiles per wave; NW waves: WM along the rows, WK along k (each takes KC / WK of a chunk's k-tiles and
+// the WK partial results are added through LDS at the end, in order), NW / (WM WK) along the row-blocks; RP: pairs
+// of row-blocks per wave; KC: k-tiles per LDS chunk; U: register slots of a wave's weight stream
+template <int NT, int WM, int NW, int WK, int RP, int KC, int U, int EPI>
 __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
-    static_assert(U % KC == 0, "a turn of the ring is a whole number of chunks");
-    constexpr int WN = NW / WM, RB = 2 * RP;
+    static_assert(KC % WK == 0, "every k-slice takes the same number of k-tiles of a chunk");
+    constexpr int KW = KC / WK;                           // k-tiles of a chunk one wave multiplies
+    static_assert(U % KW == 0, "a turn of the ring is a whole number of chunks");
+    constexpr int WN = NW / (WM * WK), RB = 2 * RP;
     constexpr int NTW = NT * WM;                          // 32-row tiles of the workgroup
     constexpr int OPS = KC * NTW * 2;                     // B operands of one plane in a chunk
     constexpr int PER_WAVE = (2 * OPS + NW - 1) / NW;     // operand loads a wave issues per chunk (both planes)
     constexpr int BUF = 2 * OPS * 1024;                   // bytes of one chunk buffer
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave / WM, wm = wave % WM;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave / (WM * WK), wm = wave % WM;
+    const int wk = WK == 1 ? 0 : __builtin_amdgcn_readfirstlane((wave / WM) % WK);
     // ---- which (row-block group bx, k-split by, row tile z)
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int z = slot % g.gz, q = (slot / g.gz) * 8 + xcd;
@@ -425,7 +429,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
         for (int p = 0; p < RP; ++p)
 #pragma unroll
             for (int op = 0; op < 2; ++op)   // a slot past the last k-tile re-reads that tile and is never used
-                abuf[u][p][op] = wp[p * wstep + (size_t)min(u, ntile - 1) * 64 + 16 * op];
+                abuf[u][p][op] = wp[p * wstep + (size_t)min((u / KW) * KC + wk * KW + u % KW, ntile - 1) * 64 + 16 * op];
 
     floatx16 acc[RP][NT];
 #pragma unroll
@@ -465,6 +469,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
         acc[p][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8 *>(&A[p][((gi) >> 1) & 1]), \
                                                            *reinterpret_cast<bf16x8 *>(&SRC[t]), acc[p][t], 0, 0, 0);
     u32x4 bv[2][NT];
+    constexpr int TURN = U / KW;   // chunks per turn of the ring
 
     // One chunk: CC (a compile-time number) places it in a turn of the weight ring, which spans U / KC chunks.
     // The next chunk's activations are requested before this chunk's MFMAs and written to LDS after them; the
@@ -477,25 +482,25 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
         const unsigned char *buf = lds + (size_t)((ch) & 1) * BUF + (size_t)(wm * NT) * 2048 + lane * 16;          \
         const int kbase = (ch) * KC;                                                                               \
         WISV_MM_STAGE_LOAD((ch) + 1)                                                                               \
-        _Pragma("unroll") for (int lt = 0; lt < KC; ++lt) {                                                        \
-            if (kbase + lt < ntile) { /* uniform; no load inside, so the load counts hold on every path */        \
+        _Pragma("unroll") for (int lw = 0; lw < KW; ++lw) {                                                        \
+            const int lt = wk * KW + lw; /* this wave's k-tile of the chunk */                                    \
+            if (kbase + lt < ntile) { /* uniform per wave; no load inside, so the load counts hold on every path */ \
                 WISV_MM_READ_B(4 * lt, bv[0])                                                                      \
                 _Pragma("unroll") for (int og = 0; og < 4; ++og) {                                                 \
                     if (og < 3) { WISV_MM_READ_B(4 * lt + og + 1, bv[(og + 1) & 1]) }                              \
                     __builtin_amdgcn_sched_barrier(0);                                                             \
-                    WISV_MM_GROUP(4 * lt + og, abuf[(CC) * KC + lt], bv[og & 1])                                   \
+                    WISV_MM_GROUP(og, abuf[(CC) * KW + lw], bv[og & 1])                                            \
                     __builtin_amdgcn_sched_barrier(0);                                                             \
                 }                                                                                                  \
             }                                                                                                      \
             /* refill the slot right after its use; past the end the last tile is re-read into a slot nobody uses */ \
             _Pragma("unroll") for (int p = 0; p < RP; ++p) _Pragma("unroll") for (int op = 0; op < 2; ++op)        \
-                abuf[(CC) * KC + lt][p][op] = wp[p * wstep + (size_t)min(kbase + lt + U, ntile - 1) * 64 + 16 * op]; \
+                abuf[(CC) * KW + lw][p][op] = wp[p * wstep + (size_t)min(kbase + lt + TURN * KC, ntile - 1) * 64 + 16 * op]; \
             __builtin_amdgcn_sched_barrier(0);                                                                     \
         }                                                                                                          \
         WISV_MM_STAGE_STORE((ch) + 1)                                                                              \
     }
 
-    constexpr int TURN = U / KC;   // chunks per turn of the ring
     const int nchunk = (ntile + KC - 1) / KC;
     WISV_MM_STAGE_LOAD(0)
     WISV_MM_STAGE_STORE(0)
@@ -512,6 +517,38 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
 #undef WISV_MM_STAGE_STORE
 #undef WISV_MM_READ_B
 #undef WISV_MM_GROUP
+    if (WK > 1) {
+        // the k-slices of a tile are added in slice order through LDS (the staging buffers are free after a barrier)
+        floatx4 *red = reinterpret_cast<floatx4 *>(lds);   // [WN WM][RP][NT][4][64]
+        const int grp = wn * WM + wm;
+        for (int sl = 1; sl < WK; ++sl) {
+            __syncthreads();
+            if (wk == sl) {
+#pragma unroll
+                for (int p = 0; p < RP; ++p)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            red[((((size_t)grp * RP + p) * NT + t) * 4 + e) * 64 + lane] =
+                                floatx4{acc[p][t][4 * e], acc[p][t][4 * e + 1], acc[p][t][4 * e + 2], acc[p][t][4 * e + 3]};
+            }
+            __syncthreads();
+            if (wk == 0) {
+#pragma unroll
+                for (int p = 0; p < RP; ++p)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const floatx4 v = red[((((size_t)grp * RP + p) * NT + t) * 4 + e) * 64 + lane];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) acc[p][t][4 * e + c] += v[c];
+                        }
+            }
+        }
+        if (wk != 0) return;
+    }
     if (!active) return;
     mm_epilogue<NT, RP, EPI>(g, acc, m_base + wm * (32 * NT), rb0, by, bx * WN + wn, lane);
 }
@@ -590,22 +627,23 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
 constexpr int MM_RP = 2;            // pairs of row-blocks per wave of k_gemm_mm
 constexpr int MM_RB = 2 * MM_RP;
 
-template <int NT, int WM, int NW, int KC, int U, int EPI>
+template <int NT, int WM, int NW, int WK, int KC, int U, int EPI>
 static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
-    constexpr int WN = NW / WM, NTW = NT * WM;
+    constexpr int WN = NW / (WM * WK), NTW = NT * WM;
     g.gx = (g.nrb + WN * MM_RB - 1) / (WN * MM_RB);
     g.gz = (g.M + 32 * NTW - 1) / (32 * NTW);
     g.gs = splits;
-    const size_t lds = (size_t)2 * 2 * KC * NTW * 2 * 1024;   // two buffers, two planes, 2 operands per (k-tile, row tile)
+    // two buffers, two planes, 2 operands per (k-tile, row tile); or the k-slice reduction: one accumulator set per tile group
+    const size_t lds = std::max((size_t)2 * 2 * KC * NTW * 2 * 1024, WK > 1 ? (size_t)WN * WM * MM_RP * NT * 4096 : (size_t)0);
     static bool opted_in = false;     // per instantiation
     if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, MM_RP, KC, U, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return false;
         opted_in = true;
     }
     const unsigned grid = (unsigned)((g.gx * g.gs + 7) / 8 * 8 * g.gz);
-    hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, MM_RP, KC, U, EPI>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
+    hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
     return true;
 }
 
@@ -615,8 +653,13 @@ static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
 // but half as many workgroups), or - "narrow" - by 2 x 2 waves (128 weight rows; two workgroups share a CU).
 // Wide pays when it still fills the chip (>= 200 workgroups) and, with k-splits, a split keeps >= 24 k-tiles;
 // narrow when a product without k-splits would otherwise leave CUs idle.
-enum { MM_NARROW = 0, MM_NORMAL = 1, MM_WIDE = 2 };   // 2 x 2, 4 x 2, 8 x 1 waves for more than 64 rows
+// A product without k-splits over at most 64 rows and few row-blocks (gate/up) would fill a quarter of the chip
+// that way: "k-slice" workgroups cover 128 weight rows only and their waves split each chunk's k-tiles among them
+// (98.9 -> 50.5 us at 32 rows, 116.9 -> 76.8 us at 64).  Beyond 64 rows workgroups that narrow re-read the
+// activations so often that the L2 fabric binds, and the shape gains nothing.
+enum { MM_NARROW = 0, MM_NORMAL = 1, MM_WIDE = 2, MM_KSLICE = 3 };   // 2 x 2, 4 x 2, 8 x 1 waves for more than 64 rows
 static int mm_layout(int rows, int nrb, int nkt, bool can_split, int max_splits) {
+    if (!can_split && rows <= 64 && (nrb + 8 * MM_RB - 1) / (8 * MM_RB) < 200) return MM_KSLICE;
     if (rows <= 64) return MM_NORMAL;
     const int tiles = (rows + 127) / 128;
     const int base8 = ((nrb + 8 * MM_RB - 1) / (8 * MM_RB)) * tiles, base4 = ((nrb + 4 * MM_RB - 1) / (4 * MM_RB)) * tiles;
@@ -633,11 +676,15 @@ static int mm_shape(int rows, int layout, int *rb_per_wg) {
 
 // More than 16 rows: k_gemm_mm
 template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits, int layout) {
-    if (g.M <= 32) return launch_mm_t<1, 1, 8, 2, 2, EPI>(c, g, splits);
-    if (g.M <= 64) return launch_mm_t<2, 1, 8, 2, 2, EPI>(c, g, splits);
-    if (layout == MM_WIDE) return launch_mm_t<4, 1, 8, 2, 2, EPI>(c, g, splits);
-    if (layout == MM_NARROW) return launch_mm_t<2, 2, 4, 2, 2, EPI>(c, g, splits);
-    return launch_mm_t<2, 2, 8, 2, 2, EPI>(c, g, splits);
+    if (layout == MM_KSLICE) {   // 2 row-block groups x 4 k-slices
+        if (g.M <= 32) return launch_mm_t<1, 1, 8, 4, 4, 4, EPI>(c, g, splits);
+        return launch_mm_t<2, 1, 8, 4, 4, 4, EPI>(c, g, splits);
+    }
+    if (g.M <= 32) return launch_mm_t<1, 1, 8, 1, 2, 2, EPI>(c, g, splits);
+    if (g.M <= 64) return launch_mm_t<2, 1, 8, 1, 2, 2, EPI>(c, g, splits);
+    if (layout == MM_WIDE) return launch_mm_t<4, 1, 8, 1, 2, 2, EPI>(c, g, splits);
+    if (layout == MM_NARROW) return launch_mm_t<2, 2, 4, 1, 2, 2, EPI>(c, g, splits);
+    return launch_mm_t<2, 2, 8, 1, 2, 2, EPI>(c, g, splits);
 }
 
 bool ws_supported(const Ctx *c, int rows, int kd) {
