@@ -170,3 +170,12 @@ def test_config1_shape_speculative_sampling_round(target8b):
     ctx.wisv_destroy()
     del kv
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("batch,k", [(8, 4), (8, 8)])
+def test_8b_shape_mid_row_counts(target8b, batch, k):
+    """32 and 64 rows at the 8B shape: the row counts between the weight-streaming kernel (at most 16 rows) and the
+    128-row tiles, where gate/up runs in the k-slice layout of the many-rows kernel."""
+    w = configs.Workload(f"mid_8b_b{batch}_l256_k{k}", 1, configs.get(1).model, batch=batch, ctx=256, k=k,
+                         protos=tuple(PROTO_FH if b % 2 == 0 else PROTO_SH for b in range(batch)), match_rate=(0.4, 0.9))
+    _run(w, target8b, sampled=[3])
