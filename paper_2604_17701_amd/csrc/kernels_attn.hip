@@ -40,8 +40,9 @@ struct AttnArgs {
     bf16_t *kv_write;         // == kv_layer
 };
 
-// NQ: 16-row query tiles; NW: waves per workgroup; FUSE: RoPE and the cache append happen here (single k-split only:
-// the one workgroup of a (stream, KV head) writes the new rows before any of its waves reads them)
+// NQ: 16-row query tiles; NW: waves per workgroup; FUSE: RoPE and the cache append happen here: every workgroup
+// rotates the queries it needs from the slices of the QKV product, and the workgroup of a (stream, KV head) whose
+// k-split ends the sequence writes the new k, v rows before any of its waves reads them (no other split reads them)
 template <int NQ, int NW, bool FUSE>
 __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -53,7 +54,20 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     const bf16_t *kc = a.kv_layer + (size_t)slot * a.slot_stride + (size_t)g * a.ctx_pad * HD;
     const bf16_t *vc = kc + (size_t)a.G * a.ctx_pad * HD;
     const int n_steps = (n_keys + STEP - 1) / STEP, sps = (n_steps + a.n_splits - 1) / a.n_splits;
-    const int s_begin = split * sps, s_end = min(n_steps, s_begin + sps);
+    int s_begin = split * sps, s_end = min(n_steps, s_begin + sps);
+    // FUSE with several k-splits: the last split appends the block's k, v rows, so it owns every step from the one
+    // that holds position L on (at most two steps more than its share); the others stop there
+    const bool appends = FUSE && split == a.n_splits - 1;
+    if (FUSE && a.n_splits > 1) {
+        const int tail = L / STEP;
+        if (appends) {
+            s_begin = min(s_begin, tail);
+            s_end = n_steps;
+        } else {
+            s_end = min(s_end, tail);
+            s_begin = min(s_begin, s_end);
+        }
+    }
 
     // ---- the first step's loads go out before anything else.  Lane (bj, bg): tile A row bj is key
     //      8 (bj / 4) + bj % 4 of the step, tile B row bj the key four further; V^T row bj of feature tile dt.
@@ -92,7 +106,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         bf16_t *kw = a.kv_write + (size_t)slot * a.slot_stride + (size_t)g * a.ctx_pad * HD;
         bf16_t *vw = kw + (size_t)a.G * a.ctx_pad * HD;
         bf16_t *q16 = reinterpret_cast<bf16_t *>(qs);
-        for (int it = tid; it < (16 * NQ + 2 * a.K) * 16; it += 64 * NW) {
+        for (int it = tid; it < (16 * NQ + (appends ? 2 * a.K : 0)) * 16; it += 64 * NW) {
             const int row = it >> 4, i = (it & 15) * 4;   // features i .. i + 3 and their partners i + 64 .. i + 67
             int j, col;                      // token of the block, first column of the head in a qkv row
             if (row < 16 * NQ) {
@@ -462,16 +476,22 @@ static int attn_splits(const Ctx *c, const Fwd &f) {
     return std::max(1, std::min(want, c->att_max_splits));
 }
 
-bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f) { return attn_splits(c, f) == 1; }
+// With several k-splits every split repeats the query part of the prologue: worth it while a round is a chain of
+// short kernels (at most 16 rows; 4.04 -> 3.92 ms at 8 rows over 4096 cached tokens), not once the slices of many
+// rows would be read by every split (96 rows, 4 splits: the attention kernel loses what the saved launch gains).
+bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f) {
+    const int s = attn_splits(c, f);
+    return s == 1 || (s > 1 && f.rows <= 16);
+}
 
 // n_partial > 0: the k-split slices of the QKV product are in c->qkv and the kernel does RoPE and the append
-// itself (only when attn_mfma_fuses_rope); n_partial == 0: launch_rope_append has run
+// itself; n_partial == 0: launch_rope_append has run
 bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial) {
     const wisv_config &g = c->cfg;
     const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
     AttnArgs a;
     a.n_splits = attn_splits(c, f);
-    if (!a.n_splits || (n_partial > 0 && a.n_splits != 1)) return false;
+    if (!a.n_splits || (n_partial > 0 && !attn_mfma_fuses_rope(c, f))) return false;
     a.q = c->q;
     a.kv_layer = (const bf16_t *)kv_ptr(c, layer, 0, 0);
     a.kv_write = (bf16_t *)kv_ptr(c, layer, 0, 0);
