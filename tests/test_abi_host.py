@@ -95,3 +95,11 @@ def test_kv_fill_follows_the_documented_cache_layout():
                 assert kv[1, 1, 1][gh, ((pos // 32) * hd + dim) * 32 + pos % 32] == v[gh, pos, dim]
                 assert kv[1, 1, 0][gh, pos * hd + dim] == k[gh, pos, dim]
     assert float(kv[0].abs().sum()) == 0.0 and float(kv[1, 0].abs().sum()) == 0.0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The round runs on one GPU: asking bench.py for more ends with a message, before anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
