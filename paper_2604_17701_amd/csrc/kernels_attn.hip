@@ -462,18 +462,17 @@ template <int NQ, int NW, bool FUSE> static bool launch_nq(Ctx *c, const AttnArg
     return true;
 }
 
-// One workgroup per (stream, KV head) when that fills the chip or the context is short - at most four steps per
-// wave - (then the workgroup
-// writes the output itself, and can do RoPE and the cache append on the way in); otherwise k-splits of at
-// least one 32-key step per wave, up to one workgroup per CU (16 streams x 8 KV heads over 2048 cached tokens:
-// 2 splits 33.5 us, 4 splits 40.8 us).  0: the shape is not served.
+// One workgroup per (stream, KV head) when that fills the chip (then the workgroup writes the output itself);
+// otherwise k-splits of at least one 32-key step per wave, up to one workgroup per CU and 16 in all (16 streams x
+// 8 KV heads over 2048 cached tokens: 2 splits 33.5 us, 4 splits 40.8 us; one stream over 512: the round takes
+// 3.51 ms with 3 splits and their combine kernel, 3.55 ms with one).  0: the shape is not served.
 static int attn_splits(const Ctx *c, const Fwd &f) {
     const wisv_config &g = c->cfg;
     const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
     if (!c->bf16 || g.head_dim != HD || R > 64 || f.rows != f.batch * f.k) return 0;
     const int nw = R <= 32 ? 8 : 4;
     const int n_steps = (f.max_len_ub + STEP - 1) / STEP, wgs = f.batch * g.n_kv_heads;
-    const int want = wgs >= 256 || n_steps <= 4 * nw ? 1 : std::min((256 + wgs - 1) / wgs, (n_steps + nw - 1) / nw);
+    const int want = wgs >= 256 ? 1 : std::min((256 + wgs - 1) / wgs, (n_steps + nw - 1) / nw);
     return std::max(1, std::min(std::min(want, 16), c->att_max_splits));   // 16: one batch of the combine kernel
 }
 
