@@ -484,9 +484,21 @@ bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f) {
     return s == 1 || (s > 1 && f.rows <= 16);
 }
 
+// c->o from the k-split partials in c->att_o / att_m / att_l
+void launch_attn_combine(Ctx *c, const Fwd &f, int n_splits) {
+    const wisv_config &g = c->cfg;
+    ProfScope ps(c, KC_ATTN_COMBINE);
+    if (n_splits <= 4)
+        hipLaunchKernelGGL(k_attn_combine<4>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
+                           n_splits, f.rows, g.n_heads, c->o);
+    else
+        hipLaunchKernelGGL(k_attn_combine<16>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
+                           n_splits, f.rows, g.n_heads, c->o);
+}
+
 // n_partial > 0: the k-split slices of the QKV product are in c->qkv and the kernel does RoPE and the append
 // itself; n_partial == 0: launch_rope_append has run
-bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial) {
+bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_combine, int *n_splits) {
     const wisv_config &g = c->cfg;
     const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
     AttnArgs a;
@@ -515,15 +527,8 @@ bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial) {
         }
         if (!ok) return false;
     }
-    if (a.n_splits > 1) {
-        ProfScope ps(c, KC_ATTN_COMBINE);
-        if (a.n_splits <= 4)
-            hipLaunchKernelGGL(k_attn_combine<4>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
-                               a.n_splits, f.rows, g.n_heads, c->o);
-        else
-            hipLaunchKernelGGL(k_attn_combine<16>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
-                               a.n_splits, f.rows, g.n_heads, c->o);
-    }
+    if (n_splits) *n_splits = a.n_splits;
+    if (a.n_splits > 1 && with_combine) launch_attn_combine(c, f, a.n_splits);
     return true;
 }
 

@@ -80,6 +80,10 @@ struct GemmArgs {
     int32_t *cand_idx;
     int n_cand;
     int gx, gz, gs;            // k_gemm_mm: row-block groups, row tiles and k-splits the 1-D grid decodes into
+    // PRO: the activations are the attention output, still in k-split partials (up to WS_PRO_SPLITS of them):
+    // o [split][rows][heads][128], running maximum m and sum l [split][rows][heads]
+    const float *att_o, *att_m, *att_l;
+    int att_splits, att_rows, att_H;
 };
 
 // ------------------------------------------------------------------------------------------ epilogues
@@ -161,8 +165,10 @@ __device__ __forceinline__ void ws_epilogue(const GemmArgs &g, floatx4 (&acc)[RB
     }
 }
 
-// NT: 16-row activation tiles per wave; RB: row-blocks per wave; WR x WK waves per workgroup; U: prefetch depth
-template <int NT, int RB, int WR, int WK, int U, int EPI>
+// NT: 16-row activation tiles per wave; RB: row-blocks per wave; WR x WK waves per workgroup; U: prefetch depth;
+// PRO: the activations are combined from the attention kernel's k-split partials while they are staged (the rule of
+// k_attn_combine: weights e^(m_s - max m), splits in index order), so that no kernel of its own has to do it
+template <int NT, int RB, int WR, int WK, int U, bool PRO, int EPI>
 __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int NTH = 64 * WR * WK;
@@ -206,10 +212,51 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
             const int w = i / per_wk, rem = i - w * per_wk, m = rem / vec_per_row, v = rem - m * vec_per_row;
             const int lt = ch * kcw + (v >> 2), kt = w * sub + lt;          // tile within the slice / the workgroup range
             if (lt < sub && kt < ntile) {
-                const size_t off = (size_t)(m_base + m) * g.kd + (size_t)(kt0 + kt) * 32 + (v & 3) * 8;
                 unsigned char *d = dst + (size_t)w * wk_bytes + (size_t)m * pitch + v * 16;
-                *reinterpret_cast<uint4 *>(d) = *reinterpret_cast<const uint4 *>(g.Xhi + off);
-                *reinterpret_cast<uint4 *>(d + plane_bytes) = *reinterpret_cast<const uint4 *>(g.Xlo + off);
+                if (PRO) {
+                    // eight consecutive features of one head (head_dim 128) of row m_base + m
+                    const int col = (kt0 + kt) * 32 + (v & 3) * 8, head = col >> 7, dd = col & 127;
+                    float ms[WS_PRO_SPLITS], ls[WS_PRO_SPLITS];
+                    floatx4 oa[WS_PRO_SPLITS], ob[WS_PRO_SPLITS];
+#pragma unroll
+                    for (int sp = 0; sp < WS_PRO_SPLITS; ++sp) {   // splits past the last re-read it and weigh zero
+                        const size_t row = ((size_t)min(sp, g.att_splits - 1) * g.att_rows + m_base + m) * g.att_H + head;
+                        ms[sp] = g.att_m[row];
+                        ls[sp] = g.att_l[row];
+                        oa[sp] = *reinterpret_cast<const floatx4 *>(g.att_o + row * 128 + dd);
+                        ob[sp] = *reinterpret_cast<const floatx4 *>(g.att_o + row * 128 + dd + 4);
+                    }
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int sp = 0; sp < WS_PRO_SPLITS; ++sp) mx = fmaxf(mx, sp < g.att_splits ? ms[sp] : -INFINITY);
+                    float den = 0.f, num[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int sp = 0; sp < WS_PRO_SPLITS; ++sp) {
+                        const bool on = sp < g.att_splits && ms[sp] != -INFINITY;
+                        const float wgt = on ? expf(ms[sp] - mx) : 0.f;
+                        den = fmaf(wgt, on ? ls[sp] : 0.f, den);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            num[e] = fmaf(wgt, on ? oa[sp][e] : 0.f, num[e]);
+                            num[4 + e] = fmaf(wgt, on ? ob[sp][e] : 0.f, num[4 + e]);
+                        }
+                    }
+                    uint32_t hw[4], lw[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        bf16_t h0, l0, h1, l1;
+                        split2(num[2 * e] / den, h0, l0);
+                        split2(num[2 * e + 1] / den, h1, l1);
+                        hw[e] = h0 | ((uint32_t)h1 << 16);
+                        lw[e] = l0 | ((uint32_t)l1 << 16);
+                    }
+                    *reinterpret_cast<uint4 *>(d) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                    *reinterpret_cast<uint4 *>(d + plane_bytes) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+                } else {
+                    const size_t off = (size_t)(m_base + m) * g.kd + (size_t)(kt0 + kt) * 32 + (v & 3) * 8;
+                    *reinterpret_cast<uint4 *>(d) = *reinterpret_cast<const uint4 *>(g.Xhi + off);
+                    *reinterpret_cast<uint4 *>(d + plane_bytes) = *reinterpret_cast<const uint4 *>(g.Xlo + off);
+                }
             }
         }
     };
@@ -599,7 +646,7 @@ static size_t ws_lds(int Mt, int kcw, int sub, int NT, int RB, int WR, int WK) {
     return std::max(x, red);
 }
 
-template <int NT, int RB, int WR, int WK, int U, int EPI>
+template <int NT, int RB, int WR, int WK, int U, int EPI, bool PRO = false>
 static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
     const int sub = (g.kt_per_split + WK - 1) / WK, Mt = std::min(g.M, 16 * NT);
     // largest chunk (a multiple of U) within the soft budget, else within what a CU has
@@ -614,13 +661,13 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
     g.kcw = kcw;
     static bool opted_in = false;     // per instantiation
     if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<NT, RB, WR, WK, U, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<NT, RB, WR, WK, U, PRO, EPI>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return false;
         opted_in = true;
     }
     dim3 grid((g.nrb / RB + WR - 1) / WR, splits, (g.M + 16 * NT - 1) / (16 * NT));
-    hipLaunchKernelGGL((k_gemm_ws<NT, RB, WR, WK, U, EPI>), grid, dim3(64 * WR * WK), lds, c->stream, g);
+    hipLaunchKernelGGL((k_gemm_ws<NT, RB, WR, WK, U, PRO, EPI>), grid, dim3(64 * WR * WK), lds, c->stream, g);
     return true;
 }
 
@@ -701,7 +748,7 @@ static void fill_args(GemmArgs &g, const void *Wt, const ActBuf &X, int rows, in
 // Y partial slices: returns the number of slices written to `Yp` ([S][split_stride]), 0 if the shape cannot
 // be served (nothing was launched)
 int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
-                           int rows, int n, int kd, int kclass) {
+                           int rows, int n, int kd, int kclass, const AttnPartials *ap) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
     fill_args(g, Wt, X, rows, n, kd);
@@ -723,6 +770,12 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
     }
     g.kt_per_split = (g.nkt + s - 1) / s;
     const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
+    if (ap) {   // the activations are the attention output, still in k-split partials
+        if (rows > 16 || ap->splits < 1 || ap->splits > WS_PRO_SPLITS || kd != ap->heads * 128) return 0;
+        g.att_o = ap->o; g.att_m = ap->m; g.att_l = ap->l;
+        g.att_splits = ap->splits; g.att_rows = ap->rows; g.att_H = ap->heads;
+        return launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL, true>(c, g, splits, 40 * 1024) ? splits : 0;
+    }
     const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
                                : launch_ws_many<EPI_PARTIAL>(c, g, splits, layout);
     return ok ? splits : 0;

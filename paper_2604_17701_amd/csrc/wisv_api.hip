@@ -407,11 +407,23 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             const LayerW &L = c->layers[l];
             launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
             const int nq = product(L.wqkv_t, L.wqkv, c->a, c->qkv, qs, c->d_qkv, d);
-            if (!(fuse_rope && launch_attn_mfma(c, f, l, nq))) {
+            // with few k-splits and few rows the O projection combines the attention partials while it stages them
+            const bool defer = fuse_rope && f.rows <= 16 && g.head_dim == 128;
+            int att_splits = 1;
+            if (!(fuse_rope && launch_attn_mfma(c, f, l, nq, !defer, &att_splits))) {
+                att_splits = 1;
                 launch_rope_append(c, f, l, nq);
                 if (!launch_attn_mfma(c, f, l, 0)) launch_attn_ref(c, f, l);
             }
-            ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
+            ny = 0;
+            if (defer && att_splits > 1) {
+                if (att_splits <= WS_PRO_SPLITS) {
+                    const AttnPartials ap{c->att_o, c->att_m, c->att_l, att_splits, f.rows, g.n_heads};
+                    ny = launch_gemm_ws_partial(c, L.wo_t, c->o, c->y, ys, MAX_SPLITS, f.rows, d, c->d_q, KC_GEMM, &ap);
+                }
+                if (!ny) launch_attn_combine(c, f, att_splits);   // more splits than the projection takes: a kernel of its own
+            }
+            if (!ny) ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
             launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
             gate_up(L);
             ny = product(L.wdown_t, L.wdown, c->h, c->y, ys, d, F);

@@ -208,8 +208,16 @@ bool ws_supported(const Ctx *c, int rows, int kd);
 int ws_padded_row_blocks(int n_rows);
 int ws_padded_pair_blocks(int features);
 void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb);
+// the attention output before its k-splits are combined: o [split][rows][heads][128], m and l [split][rows][heads]
+struct AttnPartials {
+    const float *o, *m, *l;
+    int splits, rows, heads;
+};
+constexpr int WS_PRO_SPLITS = 4;
+// ap != null: X is ignored and the activations are combined from the partials while they are staged (at most 16
+// rows and WS_PRO_SPLITS splits; 0 is returned otherwise)
 int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
-                           int rows, int n, int kd, int kclass);
+                           int rows, int n, int kd, int kclass, const AttnPartials *ap = nullptr);
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
                            int kclass);
 bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass);
@@ -217,7 +225,10 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
 // ---------------------------------------------------------------- split-KV MFMA attention (kernels_attn.hip)
 // true if the shape is served (bf16 cache, head_dim 128, at most 64 query rows per KV head); then c->o holds
 // the attention output of every row
-bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial);
+// with_combine false leaves the k-split partials in c->att_o / att_m / att_l for a consumer that combines them
+// itself (*n_splits tells how many; 1 means c->o is complete all the same)
+bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_combine = true, int *n_splits = nullptr);
+void launch_attn_combine(Ctx *c, const Fwd &f, int n_splits);
 // true if launch_attn_mfma(.., n_partial > 0) will do RoPE and the cache append itself from the k-split slices of
 // the QKV product (then launch_rope_append must not run)
 bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f);
