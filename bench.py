@@ -93,6 +93,42 @@ def measured_traffic(workload, kclass):
     return bytes_ / launches, f"profiles/{workload}_hbm_traffic.txt (FETCH_SIZE + WRITE_SIZE scaled by a copy kernel)"
 
 
+def generation_loop(ctx, w, inputs, n_rounds, binding, gen, np):
+    """n_rounds consecutive committed rounds per stream (Alg. 1's outer loop with a synthetic drafter): every block
+    starts at the stream's pending token, the other drafts follow the target's own greedy chain with the
+    workload's match rate (the chain is found with uncommitted rounds that are not timed).  Returns the average
+    accepted length (Sec. IV-C) and the time of the committed rounds, host buffers and copies included."""
+    sid = np.arange(w.batch)
+    csi, tau = inputs["csi"], inputs["tau"]
+    for b in range(w.batch):
+        ctx.wisv_set_state(b, w.ctx, inputs["pred_next"][b])
+    pending = np.asarray(inputs["pred_next"], np.int64)
+    accepted, seconds = [], 0.0
+    nc = binding.WISV_FLAG_NO_COMMIT
+    for r in range(n_rounds):
+        keep = gen.uniform01(w.seed, f"loop/keep/{r}", w.m).reshape(w.batch, w.k) < gen.match_rates(w)[:, None]
+        alt = gen.randint(w.seed, f"loop/alt/{r}", (w.batch, w.k), w.model.vocab).numpy()
+        drafts = np.zeros((w.batch, w.k), np.int32)
+        drafts[:, 0] = pending
+        for j in range(1, w.k):                       # the drafter's view of the target: one uncommitted round per position
+            t = ctx.wisv_verify_round(sid, drafts, w.protos, None, np.full(w.m, -1), csi, np.zeros(w.batch), w.k, nc)["target_argmax"][:, j]
+            drafts[:, j] = np.where(keep[:, j], t, np.where(alt[:, j] != t, alt[:, j], (alt[:, j] + 1) % w.model.vocab))
+        probe = ctx.wisv_verify_round(sid, drafts, w.protos, None, np.full(w.m, -1), csi, np.zeros(w.batch), w.k, nc)
+        mism = [[j for j in range(w.k) if (int(probe["mismatch_mask"][b]) >> j) & 1] for b in range(w.batch)]
+        hd, row_map = gen.pack_hidden(w, [gen.draft_hidden(w, b) for b in range(w.batch)], mism)
+        t0 = time.perf_counter()
+        g = ctx.wisv_verify_round(sid, drafts, w.protos, hd if hd.shape[0] else None, row_map, csi, tau, w.k, 0)
+        seconds += time.perf_counter() - t0
+        accepted.append(g["accepted_len"].copy())
+        pending = g["correction_token"].astype(np.int64)
+    acc = np.concatenate(accepted)
+    from paper_2604_17701_amd import link_model as lm
+    return {"rounds": n_rounds, "AAL": lm.average_accepted_length(acc.tolist()),
+            "ms_per_committed_round_host_io": seconds / n_rounds * 1e3,
+            "generated_tokens_per_s": float(acc.sum()) / seconds,
+            "final_context": [int(ctx.wisv_get_state(b)[0]) for b in range(min(w.batch, 4))]}
+
+
 def link_model_rows(w, t_edge, res):
     """The paper's per-round latency model (Sec. IV) with this run's measured edge time T_T + T_J plugged in, on
     two example links: which upload option the model prefers, and the modelled communication + edge latency
@@ -146,6 +182,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verifier", choices=("wisv", "ss"), default="wisv",
                     help="wisv: CSI-aware decision head (the headline path); ss: speculative sampling on the same forward")
+    ap.add_argument("--loop", type=int, default=0,
+                    help="also run N consecutive committed rounds per stream with a synthetic drafter and report the "
+                         "average accepted length (not part of the timed steps)")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="also run N plain 1 GiB copy kernels (known traffic, for scaling rocprofv3 memory counters)")
     a = ap.parse_args()
@@ -166,7 +205,7 @@ def main():
     t0 = time.time()
     wd = gen.make_weights(w.model, w.seed if a.config == 0 else configs.get(1).seed, dev)
     m = w.model
-    max_ctx = w.ctx + w.k
+    max_ctx = w.ctx + w.k + a.loop * w.k
     kv = binding.new_kv_cache(m, w.batch, max_ctx, dev)
     ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
     rnd, inputs = build_round(ctx, w, binding, gen, np, torch)
@@ -265,6 +304,8 @@ def main():
         out["spec_sampling"] = {"us_per_round": kernels["spec_sampling"]["avg_us"], "algorithmic_bytes": ss_bytes,
                                 "achieved_GBs": ss_bytes / (kernels["spec_sampling"]["avg_us"] * 1e-6) / 1e9,
                                 "logits_written_by_lm_head_bytes": w.m * m.vocab * 4}
+    if a.loop and a.verifier == "wisv":
+        out["generation_loop"] = generation_loop(ctx, w, inputs, a.loop, binding, gen, np)
     if not a.no_cpu_baseline and a.verifier == "wisv":
         t2 = time.time()
         out["cpu_baseline"] = cpu_baseline(w, wd, inputs, gen, np, torch)
