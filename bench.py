@@ -129,6 +129,26 @@ def generation_loop(ctx, w, inputs, n_rounds, binding, gen, np):
             "final_context": [int(ctx.wisv_get_state(b)[0]) for b in range(min(w.batch, 4))]}
 
 
+def profiled_duration(workload, kclass):
+    """Average duration (microseconds) rocprofv3's kernel trace gave the kernels of class `kclass` in the committed
+    summary of this workload, or None when there is none or the kernel sources changed since."""
+    from paper_2604_17701_amd import profile_summary as ps
+    stats = os.path.join(ROOT, "profiles", f"{workload}_kernel_stats.txt")
+    traffic = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    if not (os.path.exists(stats) and os.path.exists(traffic)) or ps.read_traffic(traffic)[0] != ps.source_hash():
+        return None
+    epilogue = {"gemm_qkv_o_down": "0", "gemm_gate_up": "1", "lm_head": "2"}
+    calls = total = 0.0
+    for name, (n, avg) in ps.read_kernels(stats).items():
+        base, args = ps.template_args(name)
+        hit = base == "k_attn_mfma" if kclass == "attention" else \
+            base in ("k_gemm_ws", "k_gemm_mm") and args and args[-1] == epilogue.get(kclass)
+        if hit:
+            calls += n
+            total += n * avg
+    return total / calls if calls else None
+
+
 def link_model_rows(w, t_edge, res):
     """The paper's per-round latency model (Sec. IV) with this run's measured edge time T_T + T_J plugged in, on
     two example links: which upload option the model prefers, and the modelled communication + edge latency
@@ -264,10 +284,13 @@ def main():
     per_launch = alg_bytes[dom] / k["launches_per_round"]
     achieved = per_launch / (k["avg_us"] * 1e-6) / 1e9
     traffic, traffic_note = measured_traffic(w.name, dom)
+    prof_us = profiled_duration(w.name, dom)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
                 "bytes_per_launch": per_launch, "avg_launch_us": k["avg_us"],
                 "event_pair_overhead_us": pair_us,
+                "rocprofv3_avg_launch_us": prof_us,
+                "frac_by_rocprofv3_duration": per_launch / (prof_us * 1e-6) / 1e9 / HBM_PEAK_GBS if prof_us else None,
                 "timing": f"HIP event pair around every launch on the round's stream, {a.steps} rounds right after the timed ones, "
                           "minus the duration of an empty event pair"}
     # matrix-core work of the three GEMM classes: algorithmic FLOP (2 x rows x weights) and what the two-term

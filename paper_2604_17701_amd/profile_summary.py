@@ -116,6 +116,19 @@ def read_traffic(path: str):
     return sha, table
 
 
+def read_kernels(path: str):
+    """Parses a kernel-stats summary: {kernel: (calls, average microseconds)}."""
+    table = {}
+    with open(path) as f:
+        for line in f:
+            if line.startswith("#") or " calls " not in line:
+                continue
+            name = line[:line.index(" calls ")].strip()
+            nums = line[line.index(" calls "):].split()
+            table[name] = (int(nums[1]), float(nums[3]))
+    return table
+
+
 def template_args(kernel: str):
     """'k_gemm_ws<1, 1, 8, 1, 8, 1>' -> ('k_gemm_ws', ['1', '1', '8', '1', '8', '1'])"""
     if "<" not in kernel:
