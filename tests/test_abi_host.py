@@ -103,3 +103,21 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_profile_summaries_parse_and_name_the_kernels_bench_looks_for():
+    """The committed rocprofv3 summaries are what bench.py reads its traffic and duration figures from: they must
+    parse, and hold the kernel classes of the two workloads bench.py reports them for."""
+    from paper_2604_17701_amd import profile_summary as ps
+    prof = os.path.join(ROOT, "profiles")
+    for workload, base, epi in (("cfg1_8b_b1_l512_k4", "k_gemm_ws", "1"), ("cfg4_8b_b64_l8192_k8_mixed", "k_attn_mfma", None)):
+        sha, table = ps.read_traffic(os.path.join(prof, f"{workload}_hbm_traffic.txt"))
+        kern = ps.read_kernels(os.path.join(prof, f"{workload}_kernel_stats.txt"))
+        assert sha and len(sha) == 16
+        for names in (table, kern):
+            hits = [n for n in names if ps.template_args(n)[0] == base and (epi is None or ps.template_args(n)[1][-1] == epi)]
+            assert hits, (workload, base)
+        n, fetch, write = table[hits[0]] if hits[0] in table else next(iter(table.values()))
+        assert n > 0 and fetch > 0
+    assert ps.template_args("k_gemm_ws<1, 1, 7, 1, 16, false, 1>") == ("k_gemm_ws", ["1", "1", "7", "1", "16", "false", "1"])
+    assert ps.template_args("k_decide") == ("k_decide", [])
