@@ -347,3 +347,46 @@ def test_repeated_device_round_replays_match_the_eager_round():
         for name in ("accepted_len", "correction_token", "target_argmax", "mismatch_mask", "status", "p_accept"):
             assert np.array_equal(np.asarray(got[name]).reshape(-1), np.asarray(want[name]).reshape(-1)), (it, name)
     ctx.wisv_destroy()
+
+
+@pytest.mark.parametrize("lengths,k", [((7, 300, 45), 4), ((520, 31, 33, 64), 3), ((1000, 2), 8)])
+def test_mixed_context_lengths_in_one_round(lengths, k):
+    """Streams of very different cached lengths in one round of at most 16 rows on the MFMA attention path: the
+    k-split attention (which does RoPE and the append itself) gives the tail of every stream to its last split,
+    leaves splits of short streams empty, and the O projection (or the combine kernel) merges what is there.
+    Every stream is prefilled for real on both sides and compared with the oracle."""
+    batch = len(lengths)
+    base = replace(configs.get(3), model=MID128, batch=batch, ctx=max(lengths), k=k, protos=(PROTO_FH,) * batch,
+                   kv_source="prefill", name=f"mid128_mixed_{'_'.join(map(str, lengths))}_k{k}", index=23, taus=(0.5,))
+    dev = torch.device("cuda:0")
+    wd = gen.make_weights(base.model, base.seed, dev)
+    ctx = _ctx(base, wd)
+    sides = []
+    for b, n in enumerate(lengths):
+        wb = replace(base, ctx=n)                      # the oracle side of stream b, with its own context length
+        side = OracleSide(wb, to_host_weights(wd))
+        toks = gen.context_tokens(base, b)[:n]
+        ctx.wisv_prefill(b, toks)
+        c = side.orc.new_cache(n + k)
+        side.cache[b] = c
+        side.pred_next[b] = side.orc.prefill(c, toks)
+        assert ctx.wisv_get_state(b) == (n, side.pred_next[b])
+        sides.append(side)
+    ins = [sides[b].stream_inputs(b) for b in range(batch)]
+    hd, row_map = gen.pack_hidden(base, [s.hd for s in ins], [s.mismatch for s in ins])
+    drafts = np.concatenate([s.draft for s in ins])
+    csi = gen.csi_features(base)
+    flags = binding.WISV_FLAG_NO_COMMIT | binding.WISV_FLAG_KEEP_LOGITS
+    g = ctx.wisv_verify_round(np.arange(batch), drafts, base.protos, hd, row_map, csi, np.full(batch, 0.5), k, flags)
+    check_invariants(g, drafts, k)
+    logits = ctx.wisv_debug_copy(binding.WISV_DBG_LOGITS, batch * k)
+    stats = {}
+    for b in range(batch):
+        rows = slice(b * k, (b + 1) * k)
+        o = sides[b].round(b, ins[b], PROTO_FH, hd, row_map[rows], csi[b], 0.5, want_logits=True)
+        err = row_rel_err(logits[rows], o["logits"])
+        stats["logit_rel"] = max(stats.get("logit_rel", 0.0), err)
+        assert err <= TOL_BF16.logit_rel, (b, err)
+        compare_stream(g, b, o, k, 0.5, TOL_BF16, stats, logits[rows])
+    print(f"\n[{base.name}] {stats}", flush=True)
+    ctx.wisv_destroy()
