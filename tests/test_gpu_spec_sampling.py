@@ -173,3 +173,45 @@ def test_ss_round_no_commit_and_device_io_agree():
     with pytest.raises(binding.WisvError):
         ctx.wisv_ss_verify_round(np.arange(batch), tokens, q, np.ones(batch * k, np.float32), v, k)   # u = 1 is outside [0, 1)
     ctx.wisv_destroy()
+
+
+def test_ss_round_bf16_decoder_many_rows_odd_vocabulary():
+    """A small bf16 decoder, 5 streams x 5 positions (25 rows: the many-rows GEMM writes the logits) and a
+    vocabulary of 5003 tokens (rows of the logits are not 16-byte aligned: the scalar load path of the rule's
+    kernels), checked against the oracle's forward + rule."""
+    from dataclasses import replace
+    model = replace(configs.LLAMA8B, n_layers=2, d_model=256, n_heads=2, n_kv_heads=1, head_dim=128, d_ff=688, vocab=5003,
+                    d_draft=64, d_head_hidden=32)
+    w = replace(configs.get(3), model=model, batch=5, ctx=70, k=5, protos=(0,) * 5, kv_source="prefill", index=31)
+    m, k, batch = w.model, w.k, w.batch
+    wd = gen.make_weights(m, w.seed, DEV)
+    ctx = binding.Context(m, wd, batch, w.ctx + k, k)
+    side = OracleSide(w, to_host_weights(wd))
+    pending, caches, olog = [], [], []
+    tokens = gen.randint(41, "ss_tok", (batch, k), m.vocab).numpy().astype(np.int32)
+    for b in range(batch):
+        toks = gen.context_tokens(w, b)[:w.ctx - 9 * b]
+        ctx.wisv_prefill(b, toks)
+        c = side.orc.new_cache(w.ctx + k)
+        pending.append(side.orc.prefill(c, toks))
+        caches.append(c)
+        tokens[b, 0] = pending[b]
+        for j in range(1, k):                                # drafts follow the oracle's greedy chain except one position
+            lg = side.orc.forward_block(c, len(toks), tokens[b, :j], want_logits=True)["logits"]
+            if j != 1 + b % (k - 1):
+                tokens[b, j] = int(np.argmax(lg[-1]))
+        olog.append(side.orc.forward_block(c, len(toks), tokens[b], want_logits=True)["logits"])
+    p_tok = np.array([[1.0] + [float(ss.softmax(olog[b][j - 1])[tokens[b, j]]) for j in range(1, k)] for b in range(batch)])
+    mass = np.clip(p_tok * (0.5 + 2.5 * gen.uniform01(41, "ss_mass", batch * k).reshape(batch, k)), 1e-9, 0.9)
+    q = gen.draft_distributions(41, batch * k, m.vocab, tokens.reshape(-1), mass.reshape(-1)).reshape(batch, k, -1)
+    u = gen.unit_uniforms(41, "ss_u", batch * k).reshape(batch, k)
+    v = gen.unit_uniforms(41, "ss_v", batch)
+    g = ctx.wisv_ss_verify_round(np.arange(batch), tokens, q, u, v, k, binding.WISV_FLAG_NO_COMMIT)
+    stats = {}
+    for b in range(batch):
+        check_stream(olog[b], pending[b], tokens[b], q[b], u[b], float(v[b]), int(g["accepted_len"][b]),
+                     int(g["correction_token"][b]), g["alpha"][b], 1e-3, stats)
+    stats["A"] = g["accepted_len"].tolist()
+    print(f"\n[ss_round bf16 25 rows] {stats}", flush=True)
+    assert stats.get("a_inside_margin", 0) <= 1
+    ctx.wisv_destroy()
