@@ -71,7 +71,9 @@ typedef enum { WISV_ACT_SILU = 0, WISV_ACT_RELU = 1 /* eq. mlp_form */ } wisv_ac
  * those of plain greedy verification (no hidden state has been uploaded yet).  DECIDE_ONLY, given next for the
  * same streams, k and draft tokens, skips the forward: it runs the decision head on the rows uploaded now, the
  * first-reject scan and the commit.  Both together, or DECIDE_ONLY without a matching VERIFY_ONLY before it, are
- * errors (WISV_EINVAL / WISV_ESTATE). */
+ * errors (WISV_EINVAL / WISV_ESTATE).  The pending round lives in the ctx's scratch: any other round, a
+ * wisv_prefill, wisv_set_state or wisv_kv_import on this ctx between the two calls drops it, and the DECIDE_ONLY
+ * call then fails with WISV_ESTATE (run VERIFY_ONLY again).  wisv_get_state and wisv_kv_export leave it alone. */
 #define WISV_FLAG_VERIFY_ONLY 16u
 #define WISV_FLAG_DECIDE_ONLY 32u
 
@@ -84,8 +86,10 @@ typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff, vocab;
     float rms_eps, rope_theta;
     int32_t dtype;   /* wisv_dtype: storage type of every weight, of the KV cache and of h^D.
-                        Arithmetic: WISV_F32 all float; WISV_BF16 bf16 matrix-product operands,
-                        float accumulation, float residual stream / softmax / decision head. */
+                        Arithmetic: WISV_F32 all float.  WISV_BF16: weights and cached k, v are bf16 values;
+                        activations stay float (residual stream, norms, softmax, decision head) and enter
+                        the matrix cores as two bf16 terms x = hi + lo (|x - hi - lo| <= 2^-17 |x|), one
+                        MFMA each, accumulated in float. */
     int32_t d_draft; /* width of a drafter hidden state h^D */
     int32_t d_csi;   /* number of CSI features (1..16) */
     int32_t d_head_hidden; /* d_J, hidden width of the decision head */

@@ -796,6 +796,7 @@ extern "C" int wisv_set_state(wisv_ctx *ctx, int32_t stream_id, int32_t kv_len, 
     HIP_TRY(c, hipMemcpyAsync(c->d_pred_next + stream_id, &pred_next, 4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->h_len_ub[stream_id] = kv_len;
+    c->pending_valid = false;   // a VERIFY_ONLY round decided after a state change would commit against another state
     return WISV_OK;
 }
 
@@ -825,6 +826,7 @@ extern "C" int wisv_prefill(wisv_ctx *ctx, int32_t stream_id, const int32_t *tok
     int32_t len = 0;
     if (int rc = wisv_get_state(ctx, stream_id, &len, nullptr)) return rc;
     if (len + n > g.max_ctx) return fail(c, WISV_ESTATE, "prefill of %d tokens at length %d exceeds max_ctx %d", n, len, g.max_ctx);
+    c->pending_valid = false;   // the forward below overwrites h^T, the greedy tokens and the row map a VERIFY_ONLY call left
     HIP_TRY(c, hipMemcpyAsync(c->d_stream_ids, &stream_id, 4, hipMemcpyHostToDevice, c->stream));
     const int chunk = c->rows_max;
     for (int c0 = 0; c0 < n; c0 += chunk) {
@@ -854,6 +856,7 @@ static int kv_copy(Ctx *c, int32_t stream_id, int32_t layer, void *host_k, void 
     if (len < 0 || len > g.max_ctx) return fail(c, WISV_EINVAL, "len %d outside [0, max_ctx]", len);
     if (!host_k || !host_v) return fail(c, WISV_EINVAL, "host buffer is NULL");
     if (len == 0) return WISV_OK;
+    if (to_device) c->pending_valid = false;   // the cache a pending VERIFY_ONLY round ran against is being replaced
     HIP_TRY(c, hipSetDevice(g.device_id));
     const size_t row = (size_t)g.head_dim * c->esz;
     // K: device pitch ctx_pad rows per head, host pitch len rows per head

@@ -183,6 +183,39 @@ def test_selective_hidden_protocol_in_two_calls():
     ctx.wisv_destroy()
 
 
+@pytest.mark.parametrize("between", ["prefill", "set_state", "kv_import"])
+def test_two_call_protocol_refuses_a_decide_after_the_state_moved(between):
+    """Between the two calls of the selective-hidden protocol (Alg. 1: RequestHidden(S) is a network round trip)
+    a server may admit another stream.  A prefill runs the forward over the scratch the pending round left
+    (h^T, greedy tokens, row map); set_state / kv_import change what the round was verified against.  The
+    decide call must then be refused instead of deciding from another forward's values."""
+    dev = torch.device("cuda:0")
+    w = replace(W0, protos=(PROTO_SH,))
+    wd = gen.make_weights(w.model, w.seed, dev)
+    ctx = _ctx(w, wd, max_batch=2)
+    ctx.wisv_prefill(0, gen.context_tokens(w, 0))
+    k, csi = w.k, gen.csi_features(w)
+    draft = gen.build_drafts(w, 0, None)
+    first = ctx.wisv_verify_round([0], draft, [PROTO_SH], None, np.full(k, -1), csi, [0.5], k, binding.WISV_FLAG_VERIFY_ONLY)
+    state0 = ctx.wisv_get_state(0)                      # reading the state does not disturb the pending round
+    if between == "prefill":
+        ctx.wisv_prefill(1, gen.context_tokens(w, 0)[:9])
+    elif between == "set_state":
+        ctx.wisv_set_state(1, 0, 3)
+    else:
+        kk, vv = ctx.wisv_kv_export(0, 0, 4)
+        ctx.wisv_kv_import(1, 0, kk, vv)
+    s = [j for j in range(k) if (int(first["mismatch_mask"][0]) >> j) & 1]
+    rows = np.full(k, -1, np.int32)
+    rows[s] = np.arange(len(s))
+    hd = gen.draft_hidden(w, 0)
+    with pytest.raises(binding.WisvError) as e:
+        ctx.wisv_verify_round([0], draft, [PROTO_SH], hd[s] if s else None, rows, csi, [0.5], k, binding.WISV_FLAG_DECIDE_ONLY)
+    assert e.value.code == binding.WISV_ESTATE
+    assert ctx.wisv_get_state(0) == state0              # nothing was committed
+    ctx.wisv_destroy()
+
+
 def test_commit_advances_the_stream_state():
     dev = torch.device("cuda:0")
     w = W0
