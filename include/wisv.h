@@ -225,6 +225,20 @@ int wisv_ss_decide(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab, const
                    const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *emitted_token,
                    float *alpha);
 
+/* wisv_ss_decide for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results; the kernels' scratch (chunk
+ * statistics, normalisers, chunk weights: about 2 MiB) is a static array inside the library instead of memory of
+ * the ctx, so the sizes are bounded by that array and not by the ctx: batch * k <= 1024, k <= WISV_MAX_K,
+ * vocab <= 262144 (WISV_EUNSUPPORTED beyond).  The call allocates and frees nothing, on the device or through any
+ * library; each GPU holds its copy of the array from library load to process end, and wisv_ctx_create looks its
+ * address up for the ctx's device.  All calls on one GPU share that array, whatever their ctx: calls that overlap
+ * in time on one GPU (two streams, two threads) race on it and must be serialised by the caller.  Nothing in it
+ * needs clearing between calls (every kernel writes what the next reads). */
+int wisv_ss_decide_static(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab, const float *logits,
+                          const int32_t *pending_tokens, const int32_t *draft_tokens, const float *draft_probs,
+                          const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *emitted_token,
+                          float *alpha);
+
 /* Frees everything the ctx owns (not the borrowed stream / cache).  NULL is a no-op. */
 int wisv_destroy(wisv_ctx *ctx);
 

@@ -29,7 +29,7 @@ WISV_MAX_K = 16
 EXPORTS = ("wisv_ctx_create", "wisv_verify_round", "wisv_destroy", "wisv_prefill", "wisv_set_state",
            "wisv_get_state", "wisv_kv_import", "wisv_kv_export", "wisv_debug_copy", "wisv_last_round_ms",
            "wisv_profile_enable", "wisv_profile_collect", "wisv_profile_read", "wisv_calibration_copy", "wisv_last_error",
-           "wisv_ss_verify_round", "wisv_ss_decide")
+           "wisv_ss_verify_round", "wisv_ss_decide", "wisv_ss_decide_static")
 
 
 class WisvError(RuntimeError):
@@ -105,6 +105,7 @@ def load_library() -> C.CDLL:
         lib.wisv_last_error.argtypes = [C.c_void_p]
         lib.wisv_ss_verify_round.argtypes = [C.c_void_p, C.POINTER(wisv_ss_in), C.POINTER(wisv_ss_out)]
         lib.wisv_ss_decide.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 9
+        lib.wisv_ss_decide_static.argtypes = lib.wisv_ss_decide.argtypes
         lib.wisv_last_error.restype = C.c_char_p
         for name in EXPORTS:
             if name != "wisv_last_error":
@@ -279,10 +280,12 @@ class Context:
         return SsDeviceRound(self, stream_ids, draft_tokens, draft_probs, u_accept, u_sample, k, flags)
 
     def wisv_ss_decide(self, logits: torch.Tensor, pending_tokens: torch.Tensor, draft_tokens: torch.Tensor,
-                       draft_probs: torch.Tensor, u_accept: torch.Tensor, u_sample: torch.Tensor, k: int):
+                       draft_probs: torch.Tensor, u_accept: torch.Tensor, u_sample: torch.Tensor, k: int, out=None,
+                       entry: str = "wisv_ss_decide"):
         """The rule alone on device tensors: logits, draft_probs float [batch*k, vocab]; pending_tokens int32
         [batch]; draft_tokens int32 [batch*k]; u_accept float [batch*k]; u_sample float [batch].
-        Returns device tensors (accepted_len, emitted_token, alpha); enqueue only."""
+        Returns device tensors (accepted_len, emitted_token, alpha); enqueue only.  `out`: the three output
+        tensors, when the caller already holds them (then nothing is allocated here either)."""
         rows, vocab = logits.shape
         b = rows // k
         want = ((logits, torch.float32, rows * vocab), (draft_probs, torch.float32, rows * vocab),
@@ -291,14 +294,19 @@ class Context:
         for t, dt, n in want:
             if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and t.numel() == n):
                 raise ValueError("wisv_ss_decide takes contiguous CUDA tensors of the documented types and sizes")
-        alen = torch.zeros(b, dtype=torch.int32, device=logits.device)
-        tok = torch.zeros(b, dtype=torch.int32, device=logits.device)
-        alpha = torch.zeros(rows, dtype=torch.float32, device=logits.device)
+        if out is None:
+            out = (torch.zeros(b, dtype=torch.int32, device=logits.device), torch.zeros(b, dtype=torch.int32, device=logits.device),
+                   torch.zeros(rows, dtype=torch.float32, device=logits.device))
+        alen, tok, alpha = out
         torch.cuda.current_stream(logits.device).synchronize()   # the inputs may come from another stream
-        self._check(self._lib.wisv_ss_decide(self._h, b, k, vocab, logits.data_ptr(), pending_tokens.data_ptr(),
-                                             draft_tokens.data_ptr(), draft_probs.data_ptr(), u_accept.data_ptr(),
-                                             u_sample.data_ptr(), alen.data_ptr(), tok.data_ptr(), alpha.data_ptr()))
+        self._check(getattr(self._lib, entry)(self._h, b, k, vocab, logits.data_ptr(), pending_tokens.data_ptr(),
+                                              draft_tokens.data_ptr(), draft_probs.data_ptr(), u_accept.data_ptr(),
+                                              u_sample.data_ptr(), alen.data_ptr(), tok.data_ptr(), alpha.data_ptr()))
         return alen, tok, alpha.view(b, k)
+
+    def wisv_ss_decide_static(self, *args, **kw):
+        """wisv_ss_decide on the library's static scratch (the entry point that allocates nothing)."""
+        return self.wisv_ss_decide(*args, entry="wisv_ss_decide_static", **kw)
 
     # ---------------------------------------------------------------- state
     def wisv_prefill(self, stream_id: int, tokens):

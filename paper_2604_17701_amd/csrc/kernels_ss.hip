@@ -235,12 +235,13 @@ size_t ss_workspace_bytes(int rows, int vocab, int batch) {
     return (size_t)rows * C * 8 + (size_t)rows * 16 + (size_t)batch * 8 + (size_t)batch * C * 8 + 64;
 }
 
-void launch_ss(Ctx *c, const SsArgs &a) {
+// the four kernels on `stream`, with their scratch carved from `ws` (at least ss_workspace_bytes(rows, vocab, batch))
+static void enqueue_ss(hipStream_t stream, const SsArgs &a, void *ws, int max_batch, int32_t *d_kv_len, int32_t *d_pred_next) {
     const int rows = a.batch * a.k, V = a.vocab;
     const int C = (V + SS_THREADS * SS_PER_THREAD - 1) / (SS_THREADS * SS_PER_THREAD);
     const bool vec = (V & 3) == 0 && V >= 4 && ((uintptr_t)a.logits & 15) == 0 && ((uintptr_t)a.draft_probs & 15) == 0;
     // carve the workspace: doubles first
-    char *p = (char *)c->ss_ws;
+    char *p = (char *)ws;
     double *row_z = (double *)p;  p += (size_t)rows * 8;
     double *mass = (double *)p;   p += (size_t)a.batch * C * 8;
     float *pm = (float *)p;       p += (size_t)rows * C * 4;
@@ -248,16 +249,56 @@ void launch_ss(Ctx *c, const SsArgs &a) {
     float *row_m = (float *)p;    p += (size_t)rows * 4;
     int32_t *sel_row = (int32_t *)p;  p += (size_t)a.batch * 4;
     int32_t *sel_mode = (int32_t *)p;
-    ProfScope ps(c, KC_SS);
-    hipLaunchKernelGGL(k_ss_stats, dim3(C, rows), dim3(SS_THREADS), 0, c->stream, a.logits, V, C, vec, pm, pz);
-    hipLaunchKernelGGL(k_ss_accept, dim3(a.batch), dim3(64 * a.k), 0, c->stream, a.k, V, C, c->cfg.max_batch, a.logits, pm, pz,
-                       a.stream_ids, c->d_pred_next, a.pending_tokens, a.tokens, a.draft_probs, a.u_accept, row_m, row_z,
+    hipLaunchKernelGGL(k_ss_stats, dim3(C, rows), dim3(SS_THREADS), 0, stream, a.logits, V, C, vec, pm, pz);
+    hipLaunchKernelGGL(k_ss_accept, dim3(a.batch), dim3(64 * a.k), 0, stream, a.k, V, C, max_batch, a.logits, pm, pz,
+                       a.stream_ids, d_pred_next, a.pending_tokens, a.tokens, a.draft_probs, a.u_accept, row_m, row_z,
                        sel_row, sel_mode, a.accepted_len, a.emitted_token, a.alpha);
-    hipLaunchKernelGGL(k_ss_mass, dim3(C, a.batch), dim3(SS_THREADS), 0, c->stream, V, C, rows, vec, a.logits, a.draft_probs,
+    hipLaunchKernelGGL(k_ss_mass, dim3(C, a.batch), dim3(SS_THREADS), 0, stream, V, C, rows, vec, a.logits, a.draft_probs,
                        row_m, row_z, sel_row, sel_mode, mass);
-    hipLaunchKernelGGL(k_ss_sample, dim3(a.batch), dim3(SS_THREADS), (size_t)C * 16, c->stream, V, C, rows, c->cfg.max_batch, vec,
+    hipLaunchKernelGGL(k_ss_sample, dim3(a.batch), dim3(SS_THREADS), (size_t)C * 16, stream, V, C, rows, max_batch, vec,
                        a.commit ? 1 : 0, a.logits, a.draft_probs, row_m, row_z, sel_row, sel_mode, mass, a.u_sample,
-                       a.stream_ids, a.accepted_len, a.emitted_token, c->d_kv_len, c->d_pred_next);
+                       a.stream_ids, a.accepted_len, a.emitted_token, d_kv_len, d_pred_next);
+}
+
+void launch_ss(Ctx *c, const SsArgs &a) {
+    ProfScope ps(c, KC_SS);
+    enqueue_ss(c->stream, a, c->ss_ws, c->cfg.max_batch, c->d_kv_len, c->d_pred_next);
+}
+
+// ------------------------------------------------------------------------------------------ no allocation
+// The same four kernels for callers that cannot allocate: their scratch is this array, which every device the
+// library runs on holds from the moment the library is loaded there.  `scratch` itself is only a host-side handle:
+// the device address is looked up once per device (with that device current) and kept.
+constexpr int SS_STATIC_MAX_ROWS = 1024, SS_STATIC_MAX_VOCAB = 262144, SS_STATIC_MAX_DEVICES = 64;
+constexpr size_t SS_STATIC_CHUNKS = (SS_STATIC_MAX_VOCAB + SS_THREADS * SS_PER_THREAD - 1) / (SS_THREADS * SS_PER_THREAD);
+// ss_workspace_bytes(rows, vocab, batch) at its largest (batch <= rows)
+constexpr size_t SS_STATIC_BYTES = (size_t)SS_STATIC_MAX_ROWS * SS_STATIC_CHUNKS * 8 + (size_t)SS_STATIC_MAX_ROWS * 16 +
+                                   (size_t)SS_STATIC_MAX_ROWS * 8 + (size_t)SS_STATIC_MAX_ROWS * SS_STATIC_CHUNKS * 8 + 64;
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[SS_STATIC_BYTES];
+static void *scratch_ptr[SS_STATIC_MAX_DEVICES];   // device address of `scratch` on each device, null until looked up
+
+// with `device` current; called when a context is created there.  Calls made concurrently for one device store the
+// same address.
+hipError_t ss_static_init(int device) {
+    if (device < 0 || device >= SS_STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    if (scratch_ptr[device]) return hipSuccess;
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    scratch_ptr[device] = p;
+    return hipSuccess;
+}
+
+const char *launch_ss_static(Ctx *c, const SsArgs &a) {
+    const int dev = c->cfg.device_id;
+    if ((size_t)a.batch * a.k > (size_t)SS_STATIC_MAX_ROWS) return "batch * k beyond the static scratch (1024 rows)";
+    if (a.vocab > SS_STATIC_MAX_VOCAB) return "vocab beyond the static scratch (262144 tokens)";
+    if (dev < 0 || dev >= SS_STATIC_MAX_DEVICES || !scratch_ptr[dev]) return "no static scratch address for this device";
+    if (ss_workspace_bytes(a.batch * a.k, a.vocab, a.batch) > SS_STATIC_BYTES) return "static scratch too small for these sizes";
+    // no kernel of the four reads scratch it has not written in the same call: nothing needs clearing
+    enqueue_ss(c->stream, a, scratch_ptr[dev], c->cfg.max_batch, c->d_kv_len, c->d_pred_next);
+    return nullptr;
 }
 
 }  // namespace wisv

@@ -189,6 +189,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     }
     CREATE_TRY(hipEventCreate(&c->ev_round[0]));
     CREATE_TRY(hipEventCreate(&c->ev_round[1]));
+    CREATE_TRY(ss_static_init(g.device_id));   // address of the static scratch on this device (wisv_ss_decide_static)
 
     // ---- parameters: private copies; q/k/v and gate/up are stacked so that one product serves each group
     auto copy_in = [&](void **dst, const void *src, size_t elems) -> hipError_t {
@@ -743,16 +744,22 @@ extern "C" int wisv_ss_verify_round(wisv_ctx *ctx, const wisv_ss_in *in, wisv_ss
     return WISV_OK;
 }
 
-extern "C" int wisv_ss_decide(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab, const float *logits,
-                              const int32_t *pending_tokens, const int32_t *draft_tokens, const float *draft_probs,
-                              const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *emitted_token,
-                              float *alpha) {
+static int ss_decide_common(wisv_ctx *ctx, bool static_scratch, int32_t batch, int32_t k, int32_t vocab, const float *logits,
+                            const int32_t *pending_tokens, const int32_t *draft_tokens, const float *draft_probs,
+                            const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *emitted_token,
+                            float *alpha) {
     if (!ctx) return WISV_EINVAL;
     Ctx *c = ctx;
     const wisv_config &g = c->cfg;
-    if (batch < 1 || batch > g.max_batch) return fail(c, WISV_EINVAL, "batch %d outside [1, %d]", batch, g.max_batch);
-    if (k < 1 || k > g.max_k) return fail(c, WISV_EINVAL, "k %d outside [1, max_k = %d]", k, g.max_k);
-    if (vocab < 1 || vocab > g.vocab) return fail(c, WISV_EINVAL, "vocab %d outside [1, %d] (the scratch is sized for the ctx's vocabulary)", vocab, g.vocab);
+    if (static_scratch) {
+        // sized by the library's static scratch, not by the ctx
+        if (batch < 1 || k < 1 || k > WISV_MAX_K) return fail(c, WISV_EINVAL, "batch %d / k %d outside [1, ..] / [1, %d]", batch, k, WISV_MAX_K);
+        if (vocab < 1) return fail(c, WISV_EINVAL, "vocab %d is not positive", vocab);
+    } else {
+        if (batch < 1 || batch > g.max_batch) return fail(c, WISV_EINVAL, "batch %d outside [1, %d]", batch, g.max_batch);
+        if (k < 1 || k > g.max_k) return fail(c, WISV_EINVAL, "k %d outside [1, max_k = %d]", k, g.max_k);
+        if (vocab < 1 || vocab > g.vocab) return fail(c, WISV_EINVAL, "vocab %d outside [1, %d] (the scratch is sized for the ctx's vocabulary)", vocab, g.vocab);
+    }
     if (vocab > SS_MAX_VOCAB) return fail(c, WISV_EUNSUPPORTED, "vocabulary %d beyond what the sampling kernel serves (%d)", vocab, SS_MAX_VOCAB);
     if (!logits || !pending_tokens || !draft_tokens || !draft_probs || !u_accept || !u_sample || !accepted_len ||
         !emitted_token || !alpha)
@@ -773,9 +780,29 @@ extern "C" int wisv_ss_decide(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t v
     a.emitted_token = emitted_token;
     a.alpha = alpha;
     a.commit = false;
-    launch_ss(c, a);
+    if (static_scratch) {
+        if (const char *why = launch_ss_static(c, a)) return fail(c, WISV_EUNSUPPORTED, "wisv_ss_decide_static: %s", why);
+    } else {
+        launch_ss(c, a);
+    }
     HIP_TRY(c, hipGetLastError());
     return WISV_OK;
+}
+
+extern "C" int wisv_ss_decide(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab, const float *logits,
+                              const int32_t *pending_tokens, const int32_t *draft_tokens, const float *draft_probs,
+                              const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *emitted_token,
+                              float *alpha) {
+    return ss_decide_common(ctx, false, batch, k, vocab, logits, pending_tokens, draft_tokens, draft_probs, u_accept, u_sample,
+                            accepted_len, emitted_token, alpha);
+}
+
+extern "C" int wisv_ss_decide_static(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab, const float *logits,
+                                     const int32_t *pending_tokens, const int32_t *draft_tokens, const float *draft_probs,
+                                     const float *u_accept, const float *u_sample, int32_t *accepted_len,
+                                     int32_t *emitted_token, float *alpha) {
+    return ss_decide_common(ctx, true, batch, k, vocab, logits, pending_tokens, draft_tokens, draft_probs, u_accept, u_sample,
+                            accepted_len, emitted_token, alpha);
 }
 
 // ------------------------------------------------------------------------------------------ state helpers

@@ -201,6 +201,10 @@ struct SsArgs {                    // all device pointers
 constexpr int SS_MAX_VOCAB = 4000 * 2048;   // the sampling kernel keeps one weight per 2048-token chunk in LDS
 size_t ss_workspace_bytes(int rows, int vocab, int batch);
 void launch_ss(Ctx *c, const SsArgs &a);
+// the same kernels on the library's static scratch (no allocation): ss_static_init looks its device address up once
+// per device, with that device current; launch_ss_static returns null or why the sizes are not served
+hipError_t ss_static_init(int device);
+const char *launch_ss_static(Ctx *c, const SsArgs &a);
 
 // ---------------------------------------------------------------- weight-streaming GEMM (kernels_gemm.hip)
 constexpr int MAX_SPLITS = 16;
