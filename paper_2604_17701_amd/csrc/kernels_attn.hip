@@ -37,6 +37,10 @@ struct AttnArgs {
     int n_partial;
     size_t partial_stride;
     const float *cs, *sn;     // rotary tables [max_ctx][64]
+    // FUSE, n_ss > 0: the slices are products of x * gain; row m is scaled by 1 / sqrt(sum_p ss[p][m] / d_model + eps)
+    const float *ss;          // [n_ss][rows] (always a readable address)
+    int n_ss, d_model;
+    float eps;
     bf16_t *kv_write;         // == kv_layer
 };
 
@@ -129,6 +133,9 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
                 xs[p] = *reinterpret_cast<const floatx4 *>(src + off);
                 ys[p] = *reinterpret_cast<const floatx4 *>(src + off + 64);
             }
+            float ssp[MAX_SPLITS];
+#pragma unroll
+            for (int p = 0; p < MAX_SPLITS; ++p) ssp[p] = a.ss[(size_t)min(p, max(a.n_ss, 1) - 1) * a.rows + m0 + j];
             const int pos = min(L + j, a.max_ctx - 1);
             const floatx4 co = *reinterpret_cast<const floatx4 *>(a.cs + (size_t)pos * 64 + i);
             const floatx4 si = *reinterpret_cast<const floatx4 *>(a.sn + (size_t)pos * 64 + i);
@@ -141,6 +148,14 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
                     x[c] += on ? xs[p][c] : 0.f;
                     y[c] += on ? ys[p][c] : 0.f;
                 }
+            }
+            if (a.n_ss > 0) {   // the deferred 1 / rms of the folded RMSNorm (sums of squares in slice order)
+                float t = 0.f;
+#pragma unroll
+                for (int p = 0; p < MAX_SPLITS; ++p) t += p < a.n_ss ? ssp[p] : 0.f;
+                const float inv = 1.0f / sqrtf(t / (float)a.d_model + a.eps);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) { x[c] *= inv; y[c] *= inv; }
             }
             float r0[4], r1[4];
 #pragma unroll
@@ -498,7 +513,7 @@ void launch_attn_combine(Ctx *c, const Fwd &f, int n_splits) {
 
 // n_partial > 0: the k-split slices of the QKV product are in c->qkv and the kernel does RoPE and the append
 // itself; n_partial == 0: launch_rope_append has run
-bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_combine, int *n_splits) {
+bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_combine, int *n_splits, int n_ss) {
     const wisv_config &g = c->cfg;
     const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
     AttnArgs a;
@@ -514,6 +529,8 @@ bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_
     a.o = c->o;
     a.qkv = c->qkv; a.n_partial = n_partial; a.partial_stride = (size_t)c->rows_max * c->d_qkv;
     a.cs = c->rope_cos; a.sn = c->rope_sin;
+    a.ss = c->ss; a.n_ss = n_ss; a.d_model = g.d_model; a.eps = g.rms_eps;
+    if (n_ss > 0 && n_partial == 0) return false;   // only the fused prologue applies the scale
     dim3 grid(a.n_splits, g.n_kv_heads, f.batch);
     {
         ProfScope ps(c, KC_ATTN);

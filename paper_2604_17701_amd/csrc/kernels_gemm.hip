@@ -84,7 +84,17 @@ struct GemmArgs {
     // o [split][rows][heads][128], running maximum m and sum l [split][rows][heads]
     const float *att_o, *att_m, *att_l;
     int att_splits, att_rows, att_H;
+    // PRO_NORM: the activations are the residual stream, still to be updated: v = xin + the n_partial slices of the
+    // previous product (ys), a = v * gain (the RMSNorm gain; its 1 / rms factor is applied by whoever sums this
+    // product's slices).  Workgroups with blockIdx.x == 0 also write v to xout and the sum of v^2 over their k-range
+    // to ss_out[split][row].
+    const float *xin, *ys;
+    float *xout, *ss_out;
+    const bf16_t *gain;
+    int n_partial;
+    size_t ys_stride;
 };
+enum { PRO_NONE = 0, PRO_ATTN = 1, PRO_NORM = 2 };
 
 // ------------------------------------------------------------------------------------------ epilogues
 // acc[r][t][e] = Y[m = m_base + 16 t + lane % 16][row 4 (lane / 16) + e of row-block rb0 + r]; `split` is the
@@ -166,10 +176,12 @@ __device__ __forceinline__ void ws_epilogue(const GemmArgs &g, floatx4 (&acc)[RB
 }
 
 // NT: 16-row activation tiles per wave; RB: row-blocks per wave; WR x WK waves per workgroup; U: prefetch depth;
-// PRO: the activations are combined from the attention kernel's k-split partials while they are staged (the rule of
-// k_attn_combine: weights e^(m_s - max m), splits in index order), so that no kernel of its own has to do it
-template <int NT, int RB, int WR, int WK, int U, bool PRO, int EPI>
-__global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
+// PRO_ATTN: the activations are combined from the attention kernel's k-split partials while they are staged (the rule
+// of k_attn_combine: weights e^(m_s - max m), splits in index order), so that no kernel of its own has to do it.
+// PRO_NORM: the activations are the residual stream plus the previous product's slices, times the norm gain (see
+// GemmArgs); WK == 1 and a single activation chunk
+template <int NT, int RB, int WR, int WK, int U, int PRO, int EPI>
+__global__ __launch_bounds__(64 * WR * WK, PRO == PRO_NORM ? 6 : 1) void k_gemm_ws(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int NTH = 64 * WR * WK;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave / WK, wk = wave % WK;
@@ -208,12 +220,58 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
     auto stage = [&](int ch) {
         unsigned char *dst = lds + (size_t)(ch & 1) * buf_bytes;
         const int vec_per_row = kcw * 4, per_wk = Mt * vec_per_row;
+        if (PRO == PRO_NORM) {
+            // An item is four consecutive features of one row; the four lane groups of a wave share 16 items and take
+            // four slices each (every load is unconditional: slices past the last re-read it and count as zero), then
+            // add their sums in a fixed order: ((x + s0..s3) + (s4..s7)) + ((s8..s11) + (s12..s15)).
+            float *ssq = reinterpret_cast<float *>(lds + 2 * buf_bytes);   // per item: sum of v^2
+            const int grp = lane >> 4, np = max(g.n_partial, 1);
+            const int item_per_row = kcw * 8, n_item = Mt * item_per_row;
+            for (int base = wave * 16; base < n_item; base += (NTH / 64) * 16) {
+                const int raw = base + (lane & 15), it = min(raw, n_item - 1);
+                const int m = it / item_per_row, v = it - m * item_per_row, lt = v >> 3;
+                const bool live = raw < n_item && lt < sub && lt < ntile;
+                const int col = (kt0 + min(lt, ntile - 1)) * 32 + (v & 7) * 4;
+                const size_t off = (size_t)(m_base + m) * g.kd + col;
+                const floatx4 xa = *reinterpret_cast<const floatx4 *>(g.xin + off);
+                floatx4 sa[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    sa[q] = *reinterpret_cast<const floatx4 *>(g.ys + (size_t)min(grp * 4 + q, np - 1) * g.ys_stride + off);
+                const uint2 gw = *reinterpret_cast<const uint2 *>(g.gain + col);
+                floatx4 t = grp == 0 ? xa : floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool on = grp * 4 + q < g.n_partial;   // a select: the unused re-read may hold anything
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] += on ? sa[q][e] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    t[e] += __shfl_xor(t[e], 16, 64);
+                    t[e] += __shfl_xor(t[e], 32, 64);
+                }
+                bf16_t h[4], l[4];
+                split2(t[0] * __uint_as_float(gw.x << 16), h[0], l[0]);
+                split2(t[1] * __uint_as_float(gw.x & 0xffff0000u), h[1], l[1]);
+                split2(t[2] * __uint_as_float(gw.y << 16), h[2], l[2]);
+                split2(t[3] * __uint_as_float(gw.y & 0xffff0000u), h[3], l[3]);
+                if (live) {
+                    unsigned char *d = dst + (size_t)m * pitch + v * 8;
+                    if (grp == 0) *reinterpret_cast<uint2 *>(d) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+                    if (grp == 1) *reinterpret_cast<uint2 *>(d + plane_bytes) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+                    if (grp == 2 && blockIdx.x == 0) *reinterpret_cast<floatx4 *>(g.xout + off) = t;
+                }
+                if (grp == 3 && raw < n_item) ssq[raw] = live ? (t[0] * t[0] + t[1] * t[1]) + (t[2] * t[2] + t[3] * t[3]) : 0.f;
+            }
+            return;
+        }
         for (int i = tid; i < WK * per_wk; i += NTH) {
             const int w = i / per_wk, rem = i - w * per_wk, m = rem / vec_per_row, v = rem - m * vec_per_row;
             const int lt = ch * kcw + (v >> 2), kt = w * sub + lt;          // tile within the slice / the workgroup range
             if (lt < sub && kt < ntile) {
                 unsigned char *d = dst + (size_t)w * wk_bytes + (size_t)m * pitch + v * 16;
-                if (PRO) {
+                if (PRO == PRO_ATTN) {
                     // eight consecutive features of one head (head_dim 128) of row m_base + m
                     const int col = (kt0 + kt) * 32 + (v & 3) * 8, head = col >> 7, dd = col & 127;
                     float ms[WS_PRO_SPLITS], ls[WS_PRO_SPLITS];
@@ -283,6 +341,17 @@ __global__ __launch_bounds__(64 * WR * WK) void k_gemm_ws(GemmArgs g) {
     stage(0);
     for (int ch = 0; ch < nchunk; ++ch) {
         __syncthreads();   // chunk ch is staged; everyone is done with the buffer chunk ch + 1 goes to
+        if (PRO == PRO_NORM && blockIdx.x == 0 && wave == 0) {
+            // sum of v^2 of every row over this k-range: the items of a row in index order, lanes then a fixed tree
+            const float *ssq = reinterpret_cast<const float *>(lds + 2 * buf_bytes);
+            const int item_per_row = kcw * 8;
+            for (int m = 0; m < Mt; ++m) {
+                float q2 = 0.f;
+                for (int i = lane; i < item_per_row; i += 64) q2 += ssq[m * item_per_row + i];
+                q2 = wave_sum(q2);
+                if (lane == 0) g.ss_out[(size_t)blockIdx.y * g.M + m_base + m] = q2;
+            }
+        }
         if (ch + 1 < nchunk) stage(ch + 1);
         if (!active) continue;
         const unsigned char *buf = lds + (size_t)(ch & 1) * buf_bytes + (size_t)wk * wk_bytes;
@@ -646,7 +715,7 @@ static size_t ws_lds(int Mt, int kcw, int sub, int NT, int RB, int WR, int WK) {
     return std::max(x, red);
 }
 
-template <int NT, int RB, int WR, int WK, int U, int EPI, bool PRO = false>
+template <int NT, int RB, int WR, int WK, int U, int EPI, int PRO = PRO_NONE>
 static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
     const int sub = (g.kt_per_split + WK - 1) / WK, Mt = std::min(g.M, 16 * NT);
     // largest chunk (a multiple of U) within the soft budget, else within what a CU has
@@ -656,7 +725,13 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
         while (kcw > U && ws_lds(Mt, kcw, sub, NT, RB, WR, WK) > budget) kcw = (kcw / 2 + U - 1) / U * U;
         if (ws_lds(Mt, kcw, sub, NT, RB, WR, WK) <= budget) break;
     }
-    const size_t lds = ws_lds(Mt, kcw, sub, NT, RB, WR, WK);
+    size_t lds = ws_lds(Mt, kcw, sub, NT, RB, WR, WK);
+    if (PRO == PRO_NORM) {
+        // one chunk only (the row sums of squares are taken once), and room for one float per staged item behind
+        // the two chunk buffers
+        if (sub > kcw || WK != 1) return false;
+        lds = (size_t)2 * 2 * Mt * (kcw * 64 + 16) + (size_t)Mt * kcw * 8 * 4;
+    }
     if (lds > 150 * 1024) return false;
     g.kcw = kcw;
     static bool opted_in = false;     // per instantiation
@@ -774,11 +849,32 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
         if (rows > 16 || ap->splits < 1 || ap->splits > WS_PRO_SPLITS || kd != ap->heads * 128) return 0;
         g.att_o = ap->o; g.att_m = ap->m; g.att_l = ap->l;
         g.att_splits = ap->splits; g.att_rows = ap->rows; g.att_H = ap->heads;
-        return launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL, true>(c, g, splits, 40 * 1024) ? splits : 0;
+        return launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL, PRO_ATTN>(c, g, splits, 40 * 1024) ? splits : 0;
     }
     const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
                                : launch_ws_many<EPI_PARTIAL>(c, g, splits, layout);
     return ok ? splits : 0;
+}
+
+// The product that opens a block, with the block's RMSNorm folded in (at most 16 rows): the kernel adds the previous
+// product's n_partial slices (c->y) to the residual stream x_in while it stages it, writes the sum to x_out, feeds
+// x * gain to the matrix cores and leaves the sum of squares of every row in ss[split][row]; whoever adds this
+// product's slices multiplies by 1 / sqrt(sum ss / kd + eps).  Returns the number of slices, 0 if the shape is not
+// served (nothing was launched).
+int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_out, int n_partial, const void *gain,
+                            float *Yp, size_t split_stride, int max_splits, int rows, int n, int kd, float *ss, int kclass) {
+    if (rows > 16 || n_partial > MAX_SPLITS) return 0;
+    ProfScope ps(c, kclass);
+    GemmArgs g{};
+    fill_args(g, Wt, ActBuf{nullptr, nullptr, nullptr}, rows, n, kd);
+    g.Yp = Yp; g.split_stride = split_stride;
+    int s = (6144 + g.nrb - 1) / g.nrb;
+    s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 8))));
+    g.kt_per_split = (g.nkt + s - 1) / s;
+    const int splits = (g.nkt + g.kt_per_split - 1) / g.kt_per_split;
+    g.xin = x_in; g.xout = x_out; g.ys = c->y; g.ys_stride = (size_t)c->rows_max * kd; g.n_partial = n_partial;
+    g.gain = (const bf16_t *)gain; g.ss_out = ss;
+    return launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL, PRO_NORM>(c, g, splits, 40 * 1024) ? splits : 0;
 }
 
 // gate/up with the SwiGLU fused (single split): H[rows][F] = silu(gate) * up.  Every row-block of the

@@ -189,7 +189,8 @@ void launch_gemm_ref(Ctx *c, const float *A, const void *W, float *Y, int rows, 
 template <typename WT, typename AT>
 __global__ void k_rope_append(const float *__restrict__ qkv, int n_partial, size_t partial_stride, int H, int G, int hd, const int32_t *__restrict__ row_slot,
                               const int32_t *__restrict__ row_pos, const float *__restrict__ cs,
-                              const float *__restrict__ sn, AT *q_out, WT *kv_layer, size_t slot_stride, int ctx_pad) {
+                              const float *__restrict__ sn, AT *q_out, WT *kv_layer, size_t slot_stride, int ctx_pad,
+                              const float *__restrict__ ss, int n_ss, int d_model, float eps) {
     const int m = blockIdx.x, hh = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     const int d_q = H * hd, d_kv = G * hd, pos = row_pos[m];
     const float *src = qkv + (size_t)m * (d_q + 2 * d_kv) + (size_t)hh * hd;
@@ -197,6 +198,13 @@ __global__ void k_rope_append(const float *__restrict__ qkv, int n_partial, size
     for (int p = 1; p < n_partial; ++p) {   // fixed order: slice 0 + slice 1 + ...
         a += src[p * partial_stride + i];
         b += src[p * partial_stride + i + half];
+    }
+    if (n_ss > 0) {   // the slices are products of x * gain: the deferred 1 / rms of the folded RMSNorm
+        float t = 0.f;
+        for (int p = 0; p < n_ss; ++p) t += ss[(size_t)p * gridDim.x + m];
+        const float inv = 1.0f / sqrtf(t / (float)d_model + eps);
+        a *= inv;
+        b *= inv;
     }
     const float co = cs[(size_t)pos * half + i], si = sn[(size_t)pos * half + i];
     if (hh < H) {
@@ -214,7 +222,7 @@ __global__ void k_rope_append(const float *__restrict__ qkv, int n_partial, size
     }
 }
 
-void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial) {
+void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial, int n_ss) {
     const size_t pstride = (size_t)c->rows_max * c->d_qkv;
     ProfScope ps(c, KC_ROPE);
     const wisv_config &g = c->cfg;
@@ -224,11 +232,11 @@ void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial) {
     if (c->bf16)
         hipLaunchKernelGGL((k_rope_append<bf16_t, float>), grid, block, 0, c->stream, c->qkv, n_partial, pstride, g.n_heads, g.n_kv_heads,
                            g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, c->q, (bf16_t *)kvl,
-                           slot_stride, c->ctx_pad);
+                           slot_stride, c->ctx_pad, c->ss, n_ss, g.d_model, g.rms_eps);
     else
         hipLaunchKernelGGL((k_rope_append<float, float>), grid, block, 0, c->stream, c->qkv, n_partial, pstride, g.n_heads, g.n_kv_heads,
                            g.head_dim, c->row_slot, c->row_pos, c->rope_cos, c->rope_sin, c->q, (float *)kvl,
-                           slot_stride, c->ctx_pad);
+                           slot_stride, c->ctx_pad, c->ss, n_ss, g.d_model, g.rms_eps);
 }
 
 // ------------------------------------------------------------------------------------------ attention (fallback)

@@ -321,6 +321,8 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     CREATE_TRY(dalloc(c, &c->amax, R));
     CREATE_TRY(dalloc(c, &c->scored, R));
     CREATE_TRY(dalloc(c, &c->x, (size_t)R * d));
+    CREATE_TRY(dalloc(c, &c->x_alt, (size_t)R * d));
+    CREATE_TRY(dalloc(c, &c->ss, (size_t)MAX_SPLITS * R));
     CREATE_TRY(dalloc(c, &c->y, (size_t)MAX_SPLITS * R * d));
     CREATE_TRY(dalloc(c, &c->qkv, (size_t)MAX_SPLITS * R * c->d_qkv));
     {
@@ -406,14 +408,25 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         const bool fuse_rope = attn_mfma_fuses_rope(c, f);
         for (int l = 0; l < g.n_layers; ++l) {
             const LayerW &L = c->layers[l];
-            launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
-            const int nq = product(L.wqkv_t, L.wqkv, c->a, c->qkv, qs, c->d_qkv, d);
+            // At most 16 rows, attention with the fused prologue: the attention norm is folded into the QKV product
+            // (it sums the previous slices into the residual stream itself and is fed x * gain) and the attention
+            // prologue, which sums the QKV slices anyway, applies 1 / rms.  One launch less per layer.
+            int nq = 0, n_ss = 0;
+            if (fuse_rope && f.rows <= 16) {
+                nq = n_ss = launch_gemm_ws_normfold(c, L.wqkv_t, c->x, c->x_alt, ny, L.attn_norm, c->qkv, qs, MAX_SPLITS, f.rows,
+                                                    c->d_qkv, d, c->ss, KC_GEMM);
+                if (nq) std::swap(c->x, c->x_alt);
+            }
+            if (!nq) {
+                launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
+                nq = product(L.wqkv_t, L.wqkv, c->a, c->qkv, qs, c->d_qkv, d);
+            }
             // with few k-splits and few rows the O projection combines the attention partials while it stages them
             const bool defer = fuse_rope && f.rows <= 16 && g.head_dim == 128;
             int att_splits = 1;
-            if (!(fuse_rope && launch_attn_mfma(c, f, l, nq, !defer, &att_splits))) {
+            if (!(fuse_rope && launch_attn_mfma(c, f, l, nq, !defer, &att_splits, n_ss))) {
                 att_splits = 1;
-                launch_rope_append(c, f, l, nq);
+                launch_rope_append(c, f, l, nq, n_ss);
                 if (!launch_attn_mfma(c, f, l, 0)) launch_attn_ref(c, f, l);
             }
             ny = 0;

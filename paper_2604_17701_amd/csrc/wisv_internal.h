@@ -129,6 +129,8 @@ struct Ctx {
     // scratch
     int32_t *row_slot, *row_pos, *amax, *scored;
     float *x, *y, *qkv, *gu, *h_t, *logits;   // y and qkv hold up to MAX_SPLITS partial slices
+    float *x_alt;                 // second residual-stream buffer: a product that folds the norm in reads x and writes here
+    float *ss;                    // [MAX_SPLITS][rows_max] sums of squares left by such a product
     float *cand_val;
     int32_t *cand_idx;
     float *q;                     // rotated queries [rows][d_q]
@@ -175,7 +177,8 @@ void launch_v_reblock(Ctx *c, void *rows, void *plane, int len, bool to_plane);
 void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, const ActBuf &out, float *out_f32);
 // Y[rows, n] = A[rows, kd] * W[n, kd]^T (float accumulate, float out)
 void launch_gemm_ref(Ctx *c, const float *A, const void *W, float *Y, int rows, int n, int kd, int kclass);
-void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial);
+// n_ss > 0: the slices are scaled by 1 / rms from the n_ss partial sums of squares in c->ss (folded RMSNorm)
+void launch_rope_append(Ctx *c, const Fwd &f, int layer, int n_partial, int n_ss = 0);
 void launch_attn_ref(Ctx *c, const Fwd &f, int layer);
 void launch_swiglu(Ctx *c, int rows);
 void launch_argmax(Ctx *c, int rows);
@@ -222,6 +225,8 @@ constexpr int WS_PRO_SPLITS = 4;
 // rows and WS_PRO_SPLITS splits; 0 is returned otherwise)
 int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
                            int rows, int n, int kd, int kclass, const AttnPartials *ap = nullptr);
+int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_out, int n_partial, const void *gain,
+                            float *Yp, size_t split_stride, int max_splits, int rows, int n, int kd, float *ss, int kclass);
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
                            int kclass);
 bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass);
@@ -231,7 +236,10 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
 // the attention output of every row
 // with_combine false leaves the k-split partials in c->att_o / att_m / att_l for a consumer that combines them
 // itself (*n_splits tells how many; 1 means c->o is complete all the same)
-bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_combine = true, int *n_splits = nullptr);
+// n_ss > 0: the QKV product was fed x * gain instead of RMSNorm(x); its slices are scaled by 1 / rms from the n_ss
+// partial sums of squares in c->ss (fused RoPE path only)
+bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_combine = true, int *n_splits = nullptr,
+                      int n_ss = 0);
 void launch_attn_combine(Ctx *c, const Fwd &f, int n_splits);
 // true if launch_attn_mfma(.., n_partial > 0) will do RoPE and the cache append itself from the k-split slices of
 // the QKV product (then launch_rope_append must not run)
