@@ -205,6 +205,9 @@ def main():
     ap.add_argument("--loop", type=int, default=0,
                     help="also run N consecutive committed rounds per stream with a synthetic drafter and report the "
                          "average accepted length (not part of the timed steps)")
+    ap.add_argument("--one-term", type=int, default=None,
+                    help="mask of product classes (1 QKV, 2 O, 4 gate/up, 8 down, 16 LM head) that take their activations as one "
+                         "half-precision term in rounds of more than 16 rows (default: the library's, all five)")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="also run N plain 1 GiB copy kernels (known traffic, for scaling rocprofv3 memory counters)")
     a = ap.parse_args()
@@ -228,6 +231,8 @@ def main():
     max_ctx = w.ctx + w.k + a.loop * w.k
     kv = binding.new_kv_cache(m, w.batch, max_ctx, dev)
     ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
+    if a.one_term is not None:
+        ctx.wisv_set_option(binding.WISV_OPT_ONE_TERM_CLASSES, a.one_term)
     rnd, inputs = build_round(ctx, w, binding, gen, np, torch)
     if a.verifier == "ss":
         # same drafts; drafter distributions with a small mass on the drafted token, uniform numbers as inputs

@@ -89,7 +89,8 @@ typedef struct {
                         Arithmetic: WISV_F32 all float.  WISV_BF16: weights and cached k, v are bf16 values;
                         activations stay float (residual stream, norms, softmax, decision head) and enter
                         the matrix cores as two bf16 terms x = hi + lo (|x - hi - lo| <= 2^-17 |x|), one
-                        MFMA each, accumulated in float. */
+                        MFMA each, accumulated in float.  Rounds of more than 16 rows: see
+                        WISV_OPT_ONE_TERM_CLASSES. */
     int32_t d_draft; /* width of a drafter hidden state h^D */
     int32_t d_csi;   /* number of CSI features (1..16) */
     int32_t d_head_hidden; /* d_J, hidden width of the decision head */
@@ -241,6 +242,26 @@ int wisv_ss_decide_static(wisv_ctx *ctx, int32_t batch, int32_t k, int32_t vocab
 
 /* Frees everything the ctx owns (not the borrowed stream / cache).  NULL is a no-op. */
 int wisv_destroy(wisv_ctx *ctx);
+
+/* --- options ------------------------------------------------------------------------------------ */
+
+/* WISV_OPT_ONE_TERM_CLASSES: which matrix products of the target take their activations as ONE half-precision
+ * term when a round has more than 16 rows (the regime bound by the matrix cores, Sec. IV-B's f_T with many streams).
+ * There the default for a WISV_BF16 ctx is gate/up, down and the LM head (nine tenths of the matrix work; the QKV
+ * and O products keep two terms, their rounding costs the most accuracy): each activation is rounded to an IEEE half (11
+ * significant bits; magnitudes beyond 65504 saturate) and meets the weights converted to halves (exact for
+ * |w| >= 2^-14, absolute error <= 2^-25 below; a ctx whose weights exceed the half range keeps the two-term form and
+ * refuses this option), one MFMA per operand pair instead of the two of the two-term bf16 form.  A cleared bit keeps
+ * that class on two bf16 terms (error 2^-17 per activation instead of 2^-12, twice the matrix-core work).  Rounds of
+ * at most 16 rows are bound by memory and always use two terms.  value: OR of the WISV_TERM_* bits. */
+#define WISV_OPT_ONE_TERM_CLASSES 1
+#define WISV_TERM_QKV 1
+#define WISV_TERM_O 2
+#define WISV_TERM_GATE_UP 4
+#define WISV_TERM_DOWN 8
+#define WISV_TERM_LM_HEAD 16
+int wisv_set_option(wisv_ctx *ctx, int32_t option, int64_t value);
+int wisv_get_option(wisv_ctx *ctx, int32_t option, int64_t *value);
 
 /* --- state helpers --------------------------------------------------------------------------- */
 

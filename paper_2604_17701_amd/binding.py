@@ -25,11 +25,14 @@ WISV_FLAG_VERIFY_ONLY, WISV_FLAG_DECIDE_ONLY = 16, 32
 WISV_STATUS_MISSING_HIDDEN = 1
 WISV_DBG_HIDDEN, WISV_DBG_LOGITS = 0, 1
 WISV_MAX_K = 16
+WISV_OPT_ONE_TERM_CLASSES = 1
+WISV_TERM_QKV, WISV_TERM_O, WISV_TERM_GATE_UP, WISV_TERM_DOWN, WISV_TERM_LM_HEAD = 1, 2, 4, 8, 16
+WISV_TERM_ALL = 31
 
 EXPORTS = ("wisv_ctx_create", "wisv_verify_round", "wisv_destroy", "wisv_prefill", "wisv_set_state",
            "wisv_get_state", "wisv_kv_import", "wisv_kv_export", "wisv_debug_copy", "wisv_last_round_ms",
            "wisv_profile_enable", "wisv_profile_collect", "wisv_profile_read", "wisv_calibration_copy", "wisv_last_error",
-           "wisv_ss_verify_round", "wisv_ss_decide", "wisv_ss_decide_static")
+           "wisv_ss_verify_round", "wisv_ss_decide", "wisv_ss_decide_static", "wisv_set_option", "wisv_get_option")
 
 
 class WisvError(RuntimeError):
@@ -106,6 +109,8 @@ def load_library() -> C.CDLL:
         lib.wisv_ss_verify_round.argtypes = [C.c_void_p, C.POINTER(wisv_ss_in), C.POINTER(wisv_ss_out)]
         lib.wisv_ss_decide.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 9
         lib.wisv_ss_decide_static.argtypes = lib.wisv_ss_decide.argtypes
+        lib.wisv_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
+        lib.wisv_get_option.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int64)]
         lib.wisv_last_error.restype = C.c_char_p
         for name in EXPORTS:
             if name != "wisv_last_error":
@@ -335,6 +340,15 @@ class Context:
         v = torch.empty(shape, dtype=self.torch_dtype)
         self._check(self._lib.wisv_kv_export(self._h, stream_id, layer, k.data_ptr(), v.data_ptr(), length))
         return k, v
+
+    # ---------------------------------------------------------------- options
+    def wisv_set_option(self, option: int, value: int):
+        self._check(self._lib.wisv_set_option(self._h, option, value))
+
+    def wisv_get_option(self, option: int) -> int:
+        v = C.c_int64()
+        self._check(self._lib.wisv_get_option(self._h, option, C.byref(v)))
+        return v.value
 
     # ---------------------------------------------------------------- diagnostics
     def wisv_debug_copy(self, what: int, rows: int) -> np.ndarray:

@@ -31,8 +31,10 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // pair_rows > 0: W stacks two matrices of pair_rows rows each (gate over up); row-block rb then holds
 // gate rows 8rb..8rb+7 in its rows 0..7 and up rows 8rb..8rb+7 in its rows 8..15, so that one MFMA tile
 // carries both halves of SwiGLU for 8 features.
+// overflow != null: every element is converted to an IEEE half (nearest-even; magnitudes below 2^-14 keep what a
+// subnormal half holds, an absolute error of at most 2^-25); *overflow is set when one does not fit the half range
 __global__ void k_retile(const bf16_t *__restrict__ W, int n_rows, int kd, int nrb, int nkt, int pair_rows,
-                         uint4 *__restrict__ out) {
+                         uint4 *__restrict__ out, int32_t *overflow) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)nrb * nkt * 64) return;
     const int lane = idx & 63;
@@ -50,14 +52,26 @@ __global__ void k_retile(const bf16_t *__restrict__ W, int n_rows, int kd, int n
     }
     uint4 v = make_uint4(0, 0, 0, 0);
     if (valid) v = *reinterpret_cast<const uint4 *>(W + (size_t)row * kd + 32 * kt + 8 * (lane >> 4));
+    if (overflow) {
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        bool bad = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float a = __uint_as_float(w[e] << 16), b = __uint_as_float(w[e] & 0xffff0000u);
+            bad = bad || !(fabsf(a) <= 65504.0f) || !(fabsf(b) <= 65504.0f);
+            w[e] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)a) | ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)b) << 16);
+        }
+        if (bad) atomicOr(overflow, 1);
+        v = make_uint4(w[0], w[1], w[2], w[3]);
+    }
     out[idx] = v;
 }
 
-void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb) {
+void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb, int32_t *overflow) {
     const int nkt = kd / 32;
     const size_t total = (size_t)nrb * nkt * 64;
     hipLaunchKernelGGL(k_retile, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c->stream, (const bf16_t *)W,
-                       n_rows, kd, nrb, nkt, pair_rows, (uint4 *)out);
+                       n_rows, kd, nrb, nkt, pair_rows, (uint4 *)out, overflow);
 }
 
 // row-blocks are padded to a multiple of 16 so that a workgroup may own up to 16 of them
@@ -71,6 +85,7 @@ enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
 struct GemmArgs {
     const u32x4 *Wt;           // re-tiled weights [nrb][nkt][64]
     const bf16_t *Xhi, *Xlo;   // activation planes [M][kd]
+    const uint16_t *X16;       // the activations as one half each (k_gemm_mm with ONE term; Wt then holds halves too)
     int M, N, kd, nrb, nkt, kt_per_split;
     int kcw;                   // k-tiles per wave staged in LDS at a time (a multiple of the prefetch depth)
     float *Yp;                 // EPI_PARTIAL: [S][split_stride];  EPI_ARGMAX with logits != null: [M][N]
@@ -507,7 +522,14 @@ __device__ __forceinline__ void mm_epilogue(const GemmArgs &g, floatx16 (&acc)[R
 // NT: 32-row tiles per wave; NW waves: WM along the rows, WK along k (each takes KC / WK of a chunk's k-tiles and
 // the WK partial results are added through LDS at the end, in order), NW / (WM WK) along the row-blocks; RP: pairs
 // of row-blocks per wave; KC: k-tiles per LDS chunk; U: register slots of a wave's weight stream
-template <int NT, int WM, int NW, int WK, int RP, int KC, int U, int EPI>
+// NPL: 2 = activations as two bf16 terms (planes hi and lo, two MFMAs per operand pair); 1 = one half-precision term
+// (plane X16 against half-precision weight tiles, one MFMA per pair: half the matrix-core work and half the staging)
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+template <int NPL> __device__ __forceinline__ floatx16 mm_mfma(const u32x4 &a, const u32x4 &b, const floatx16 &c) {
+    if (NPL == 2) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&a), *reinterpret_cast<const bf16x8 *>(&b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const f16x8 *>(&a), *reinterpret_cast<const f16x8 *>(&b), c, 0, 0, 0);
+}
+template <int NT, int WM, int NW, int WK, int RP, int KC, int U, int EPI, int NPL>
 __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
     static_assert(KC % WK == 0, "every k-slice takes the same number of k-tiles of a chunk");
@@ -516,8 +538,9 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     constexpr int WN = NW / (WM * WK), RB = 2 * RP;
     constexpr int NTW = NT * WM;                          // 32-row tiles of the workgroup
     constexpr int OPS = KC * NTW * 2;                     // B operands of one plane in a chunk
-    constexpr int PER_WAVE = (2 * OPS + NW - 1) / NW;     // operand loads a wave issues per chunk (both planes)
-    constexpr int BUF = 2 * OPS * 1024;                   // bytes of one chunk buffer
+    constexpr int PER_WAVE = (NPL * OPS + NW - 1) / NW;   // operand loads a wave issues per chunk (all planes)
+    constexpr int BUF = NPL * OPS * 1024;                 // bytes of one chunk buffer
+    constexpr int G = 2 * NPL;                            // operand groups (op, plane) of a k-tile
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave / (WM * WK), wm = wave % WM;
     const int wk = WK == 1 ? 0 : __builtin_amdgcn_readfirstlane((wave / WM) % WK);
     // ---- which (row-block group bx, k-split by, row tile z)
@@ -559,7 +582,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     //      ((i % OPS) / 2) % NTW, i % 2); wave w takes ids w, w + NW, ...  No load is conditional (a branch would
     //      make the compiler wait for each one at once): rows past M re-read row M - 1, k-tiles past the end
     //      re-read the last one; neither is ever used.
-    static_assert((2 * OPS) % NW == 0, "every wave stages the same number of operands");
+    static_assert((NPL * OPS) % NW == 0, "every wave stages the same number of operands");
     const int srow = m_base + (lane & 31);
     const int scol = (lane >> 5) * 16;
     u32x4 sreg[PER_WAVE];
@@ -568,22 +591,22 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
         const int i = wave + NW * j, pl = i / OPS, rem = i % OPS, lt = rem / (2 * NTW), t = (rem / 2) % NTW, op = rem & 1; \
         const int kt = min((ch) * KC + lt, ntile - 1);                                                             \
         const int row = min(srow + 32 * t, g.M - 1);                                                               \
-        sreg[j] = *reinterpret_cast<const u32x4 *>((pl ? g.Xlo : g.Xhi) + (size_t)row * g.kd +                     \
+        sreg[j] = *reinterpret_cast<const u32x4 *>((NPL == 1 ? g.X16 : pl ? g.Xlo : g.Xhi) + (size_t)row * g.kd +  \
                                                    (size_t)(kt0 + kt) * 32 + 8 * op + scol);                       \
     }
 #define WISV_MM_STAGE_STORE(ch)                                                                                    \
     _Pragma("unroll") for (int j = 0; j < PER_WAVE; ++j)                                                           \
         *reinterpret_cast<u32x4 *>(lds + (size_t)((ch) & 1) * BUF + (size_t)(wave + NW * j) * 1024 + lane * 16) = sreg[j];
-    // A k-tile is four groups (op, plane) of NT B operands, each feeding NT RP independent MFMAs.  The B
+    // A k-tile is G groups (op, plane) of NT B operands, each feeding NT RP independent MFMAs.  The B
     // operands of group gi + 1 are read from LDS before the MFMAs of group gi issue (scheduling barriers keep
     // that order): the LDS latency hides behind matrix work, the other wave of the SIMD fills what is left.
-#define WISV_MM_READ_B(gi, DST)                                                                                    \
+    // group og of k-tile lt: plane og % NPL, operand og / NPL
+#define WISV_MM_READ_B(lt, og, DST)                                                                                \
     _Pragma("unroll") for (int t = 0; t < NT; ++t)                                                                 \
-        DST[t] = *reinterpret_cast<const u32x4 *>(buf + ((((gi) & 1) * OPS) + ((((gi) >> 2) * NTW + t) * 2 + (((gi) >> 1) & 1))) * 1024);
-#define WISV_MM_GROUP(gi, A, SRC)                                                                                    \
+        DST[t] = *reinterpret_cast<const u32x4 *>(buf + ((((og) % NPL) * OPS) + (((lt) * NTW + t) * 2 + (og) / NPL)) * 1024);
+#define WISV_MM_GROUP(og, A, SRC)                                                                                  \
     _Pragma("unroll") for (int t = 0; t < NT; ++t) _Pragma("unroll") for (int p = 0; p < RP; ++p)                  \
-        acc[p][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8 *>(&A[p][((gi) >> 1) & 1]), \
-                                                           *reinterpret_cast<bf16x8 *>(&SRC[t]), acc[p][t], 0, 0, 0);
+        acc[p][t] = mm_mfma<NPL>(A[p][(og) / NPL], SRC[t], acc[p][t]);
     u32x4 bv[2][NT];
     constexpr int TURN = U / KW;   // chunks per turn of the ring
 
@@ -601,9 +624,9 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
         _Pragma("unroll") for (int lw = 0; lw < KW; ++lw) {                                                        \
             const int lt = wk * KW + lw; /* this wave's k-tile of the chunk */                                    \
             if (kbase + lt < ntile) { /* uniform per wave; no load inside, so the load counts hold on every path */ \
-                WISV_MM_READ_B(4 * lt, bv[0])                                                                      \
-                _Pragma("unroll") for (int og = 0; og < 4; ++og) {                                                 \
-                    if (og < 3) { WISV_MM_READ_B(4 * lt + og + 1, bv[(og + 1) & 1]) }                              \
+                WISV_MM_READ_B(lt, 0, bv[0])                                                                       \
+                _Pragma("unroll") for (int og = 0; og < G; ++og) {                                                 \
+                    if (og < G - 1) { WISV_MM_READ_B(lt, og + 1, bv[(og + 1) & 1]) }                               \
                     __builtin_amdgcn_sched_barrier(0);                                                             \
                     WISV_MM_GROUP(og, abuf[(CC) * KW + lw], bv[og & 1])                                            \
                     __builtin_amdgcn_sched_barrier(0);                                                             \
@@ -749,23 +772,23 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
 constexpr int MM_RP = 2;            // pairs of row-blocks per wave of k_gemm_mm
 constexpr int MM_RB = 2 * MM_RP;
 
-template <int NT, int WM, int NW, int WK, int KC, int U, int EPI>
+template <int NT, int WM, int NW, int WK, int KC, int U, int EPI, int NPL>
 static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
     constexpr int WN = NW / (WM * WK), NTW = NT * WM;
     g.gx = (g.nrb + WN * MM_RB - 1) / (WN * MM_RB);
     g.gz = (g.M + 32 * NTW - 1) / (32 * NTW);
     g.gs = splits;
     // two buffers, two planes, 2 operands per (k-tile, row tile); or the k-slice reduction: one accumulator set per tile group
-    const size_t lds = std::max((size_t)2 * 2 * KC * NTW * 2 * 1024, WK > 1 ? (size_t)WN * WM * MM_RP * NT * 4096 : (size_t)0);
+    const size_t lds = std::max((size_t)2 * NPL * KC * NTW * 2 * 1024, WK > 1 ? (size_t)WN * WM * MM_RP * NT * 4096 : (size_t)0);
     static bool opted_in = false;     // per instantiation
     if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return false;
         opted_in = true;
     }
     const unsigned grid = (unsigned)((g.gx * g.gs + 7) / 8 * 8 * g.gz);
-    hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
+    hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
     return true;
 }
 
@@ -797,16 +820,27 @@ static int mm_shape(int rows, int layout, int *rb_per_wg) {
 }
 
 // More than 16 rows: k_gemm_mm
-template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits, int layout) {
+template <int EPI, int NPL> static bool launch_ws_many_t(Ctx *c, GemmArgs &g, int splits, int layout) {
     if (layout == MM_KSLICE) {   // 2 row-block groups x 4 k-slices
-        if (g.M <= 32) return launch_mm_t<1, 1, 8, 4, 4, 4, EPI>(c, g, splits);
-        return launch_mm_t<2, 1, 8, 4, 4, 4, EPI>(c, g, splits);
+        if (g.M <= 32) return launch_mm_t<1, 1, 8, 4, 4, 4, EPI, NPL>(c, g, splits);
+        return launch_mm_t<2, 1, 8, 4, 4, 4, EPI, NPL>(c, g, splits);
     }
-    if (g.M <= 32) return launch_mm_t<1, 1, 8, 1, 2, 2, EPI>(c, g, splits);
-    if (g.M <= 64) return launch_mm_t<2, 1, 8, 1, 2, 2, EPI>(c, g, splits);
-    if (layout == MM_WIDE) return launch_mm_t<4, 1, 8, 1, 2, 2, EPI>(c, g, splits);
-    if (layout == MM_NARROW) return launch_mm_t<2, 2, 4, 1, 2, 2, EPI>(c, g, splits);
-    return launch_mm_t<2, 2, 8, 1, 2, 2, EPI>(c, g, splits);
+    if (g.M <= 32) {   // one row tile, one plane: chunks of four k-tiles give every wave an operand to stage
+        if (NPL == 1) return launch_mm_t<1, 1, 8, 1, 4, 4, EPI, NPL>(c, g, splits);
+        return launch_mm_t<1, 1, 8, 1, 2, 2, EPI, 2>(c, g, splits);
+    }
+    if (g.M <= 64) return launch_mm_t<2, 1, 8, 1, 2, 2, EPI, NPL>(c, g, splits);
+    if (layout == MM_WIDE) return launch_mm_t<4, 1, 8, 1, 2, 2, EPI, NPL>(c, g, splits);
+    if (layout == MM_NARROW) return launch_mm_t<2, 2, 4, 1, 2, 2, EPI, NPL>(c, g, splits);
+    return launch_mm_t<2, 2, 8, 1, 2, 2, EPI, NPL>(c, g, splits);
+}
+// Wh: the half-precision tiles, or null for the two-term product on the bf16 tiles already in g.Wt
+template <int EPI> static bool launch_ws_many(Ctx *c, GemmArgs &g, int splits, int layout, const void *Wh) {
+    if (Wh && g.X16) {
+        g.Wt = (const u32x4 *)Wh;
+        return launch_ws_many_t<EPI, 1>(c, g, splits, layout);
+    }
+    return launch_ws_many_t<EPI, 2>(c, g, splits, layout);
 }
 
 bool ws_supported(const Ctx *c, int rows, int kd) {
@@ -815,7 +849,7 @@ bool ws_supported(const Ctx *c, int rows, int kd) {
 
 static void fill_args(GemmArgs &g, const void *Wt, const ActBuf &X, int rows, int n, int kd) {
     g.Wt = (const u32x4 *)Wt;
-    g.Xhi = X.hi; g.Xlo = X.lo;
+    g.Xhi = X.hi; g.Xlo = X.lo; g.X16 = X.h16;
     g.M = rows; g.N = n; g.kd = kd;
     g.nrb = ws_padded_row_blocks(n); g.nkt = kd / 32;
 }
@@ -823,7 +857,7 @@ static void fill_args(GemmArgs &g, const void *Wt, const ActBuf &X, int rows, in
 // Y partial slices: returns the number of slices written to `Yp` ([S][split_stride]), 0 if the shape cannot
 // be served (nothing was launched)
 int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
-                           int rows, int n, int kd, int kclass, const AttnPartials *ap) {
+                           int rows, int n, int kd, int kclass, const AttnPartials *ap, const void *Wh) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
     fill_args(g, Wt, X, rows, n, kd);
@@ -852,7 +886,7 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
         return launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL, PRO_ATTN>(c, g, splits, 40 * 1024) ? splits : 0;
     }
     const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL>(c, g, splits, 40 * 1024)
-                               : launch_ws_many<EPI_PARTIAL>(c, g, splits, layout);
+                               : launch_ws_many<EPI_PARTIAL>(c, g, splits, layout, Wh);
     return ok ? splits : 0;
 }
 
@@ -866,7 +900,7 @@ int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_
     if (rows > 16 || n_partial > MAX_SPLITS) return 0;
     ProfScope ps(c, kclass);
     GemmArgs g{};
-    fill_args(g, Wt, ActBuf{nullptr, nullptr, nullptr}, rows, n, kd);
+    fill_args(g, Wt, ActBuf{}, rows, n, kd);
     g.Yp = Yp; g.split_stride = split_stride;
     int s = (6144 + g.nrb - 1) / g.nrb;
     s = std::max(1, std::min(s, std::min(max_splits, std::max(1, g.nkt / 8))));
@@ -880,7 +914,7 @@ int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_
 // gate/up with the SwiGLU fused (single split): H[rows][F] = silu(gate) * up.  Every row-block of the
 // re-tiled matrix holds 8 gate and 8 up rows.
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
-                           int kclass) {
+                           int kclass, const void *Wh) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
     fill_args(g, Wt, X, rows, features, kd);
@@ -894,11 +928,12 @@ bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf
         if (fill(7) > fill(8)) return launch_ws_t<1, 1, 7, 1, 16, EPI_SWIGLU>(c, g, 1, 36 * 1024);
         return launch_ws_t<1, 1, 8, 1, 16, EPI_SWIGLU>(c, g, 1, 36 * 1024);
     }
-    return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1));
+    return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1), Wh);
 }
 
 // LM head with the argmax fused: greedy token of every row in c->amax; logits kept only on request
-bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass) {
+bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass,
+                           const void *Wh) {
     GemmArgs g{};
     fill_args(g, Wt, X, rows, n, kd);
     g.kt_per_split = g.nkt;
@@ -909,7 +944,7 @@ bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logit
     {
         ProfScope ps(c, kclass);
         const bool ok = rows <= 16 ? launch_ws_t<1, 1, 8, 1, 16, EPI_ARGMAX>(c, g, 1, 70 * 1024)
-                                   : launch_ws_many<EPI_ARGMAX>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1));
+                                   : launch_ws_many<EPI_ARGMAX>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1), Wh);
         if (!ok) return false;
     }
     {

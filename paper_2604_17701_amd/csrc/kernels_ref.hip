@@ -126,6 +126,9 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restr
         split2(r.w, h[3], l[3]);
         *reinterpret_cast<uint2 *>(out.hi + (size_t)m * d + i) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
         *reinterpret_cast<uint2 *>(out.lo + (size_t)m * d + i) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+        if (out.h16)
+            *reinterpret_cast<uint2 *>(out.h16 + (size_t)m * d + i) = make_uint2(f32_to_f16(r.x) | ((uint32_t)f32_to_f16(r.y) << 16),
+                                                                                 f32_to_f16(r.z) | ((uint32_t)f32_to_f16(r.w) << 16));
         if (out_f32) *reinterpret_cast<float4 *>(out_f32 + (size_t)m * d + i) = r;
     }
 }

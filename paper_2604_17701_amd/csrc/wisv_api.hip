@@ -242,7 +242,9 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
 
     // ---- re-tiled copies for the weight-streaming MFMA GEMM (bf16, every reduction length a multiple of 32)
     c->ws_ok = c->bf16 && d % 32 == 0 && c->d_q % 32 == 0 && F % 32 == 0;
-    c->lm_head_t = nullptr;
+    c->lm_head_t = c->lm_head_h = nullptr;
+    c->half_ok = false;
+    c->one_term_mask = 0;
     if (c->ws_ok) {
         auto retile = [&](void **dst, const void *src, int n_rows, int kd, int pair_rows) -> hipError_t {
             const int nrb = pair_rows > 0 ? ws_padded_pair_blocks(pair_rows) : ws_padded_row_blocks(n_rows);
@@ -253,6 +255,42 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
             launch_retile(c, src, n_rows, kd, pair_rows, p, nrb);
             return hipGetLastError();
         };
+        // the same tiles as IEEE halves when rounds of more than 16 rows can occur: there the products are bound by
+        // the matrix cores and take their activations as one half-precision term instead of two bf16 terms
+        const bool want_half = R > 16;
+        int32_t *d_overflow = nullptr;
+        if (want_half) {
+            CREATE_TRY(dalloc(c, &d_overflow, 1));
+            CREATE_TRY(hipMemsetAsync(d_overflow, 0, 4, c->stream));
+        }
+        auto retile_h = [&](void **dst, const void *src, int n_rows, int kd, int pair_rows) -> hipError_t {
+            *dst = nullptr;
+            if (!want_half) return hipSuccess;
+            const int nrb = pair_rows > 0 ? ws_padded_pair_blocks(pair_rows) : ws_padded_row_blocks(n_rows);
+            char *p;
+            hipError_t e = dalloc(c, &p, (size_t)nrb * 16 * kd * 2);
+            if (e != hipSuccess) return e;
+            *dst = p;
+            launch_retile(c, src, n_rows, kd, pair_rows, p, nrb, d_overflow);
+            return hipGetLastError();
+        };
+        CREATE_TRY(retile_h(&c->lm_head_h, c->lm_head, V, d, 0));
+        for (int l = 0; l < g.n_layers; ++l) {
+            LayerW &L = c->layers[l];
+            CREATE_TRY(retile_h(&L.wqkv_h, L.wqkv, c->d_qkv, d, 0));
+            CREATE_TRY(retile_h(&L.wo_h, L.wo, d, c->d_q, 0));
+            CREATE_TRY(retile_h(&L.wgu_h, L.wgu, 2 * F, d, F));
+            CREATE_TRY(retile_h(&L.wdown_h, L.wdown, d, F, 0));
+        }
+        if (want_half) {
+            int32_t overflow = 0;
+            CREATE_TRY(hipMemcpyAsync(&overflow, d_overflow, 4, hipMemcpyDeviceToHost, c->stream));
+            CREATE_TRY(hipStreamSynchronize(c->stream));
+            c->half_ok = overflow == 0;   // a weight beyond the half range: stay with two bf16 terms everywhere
+        }
+        // default: the feed-forward products and the LM head (9/10 of the matrix work).  The QKV and O products keep
+        // two terms: their rounding passes through the softmax and costs the most accuracy per unit of work saved.
+        c->one_term_mask = c->half_ok ? (TERM_GATE_UP | TERM_DOWN | TERM_LM_HEAD) : 0;
         CREATE_TRY(retile(&c->lm_head_t, c->lm_head, V, d, 0));
         CREATE_TRY(retile(&c->head_w1_t, c->head_w1_pad, g.d_head_hidden, c->din_pad, 0));
         for (int l = 0; l < g.n_layers; ++l) {
@@ -333,16 +371,18 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     CREATE_TRY(dalloc(c, &c->gu, (size_t)R * 2 * F));
     CREATE_TRY(dalloc(c, &c->h_t, (size_t)R * d));
     CREATE_TRY(dalloc(c, &c->hu, (size_t)MAX_SPLITS * R * g.d_head_hidden));
-    auto act_alloc = [&](ActBuf *a, size_t n) -> hipError_t {
+    auto act_alloc = [&](ActBuf *a, size_t n, bool half) -> hipError_t {
         hipError_t e = dalloc(c, &a->f, n);
         if (e == hipSuccess) e = dalloc(c, &a->hi, n);
         if (e == hipSuccess) e = dalloc(c, &a->lo, n);
+        a->h16 = nullptr;
+        if (e == hipSuccess && half) e = dalloc(c, &a->h16, n);
         return e;
     };
-    CREATE_TRY(act_alloc(&c->a, (size_t)R * d));
-    CREATE_TRY(act_alloc(&c->o, (size_t)R * c->d_q));
-    CREATE_TRY(act_alloc(&c->h, (size_t)R * F));
-    CREATE_TRY(act_alloc(&c->z, (size_t)R * c->din_pad));
+    CREATE_TRY(act_alloc(&c->a, (size_t)R * d, c->half_ok));
+    CREATE_TRY(act_alloc(&c->o, (size_t)R * c->d_q, c->half_ok));
+    CREATE_TRY(act_alloc(&c->h, (size_t)R * F, c->half_ok));
+    CREATE_TRY(act_alloc(&c->z, (size_t)R * c->din_pad, false));
     CREATE_TRY(dalloc(c, &c->q, (size_t)R * c->d_q));
     {
         // split-KV attention partials: as many splits as fit 64 MiB, at most 64
@@ -390,8 +430,10 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         // kernel sums in a fixed order; gate/up and the LM head fuse SwiGLU / argmax instead
         const size_t ys = (size_t)c->rows_max * d, qs = (size_t)c->rows_max * c->d_qkv;
         // a product whose shape the streaming kernel cannot serve falls back to the generic kernel (one slice)
-        auto product = [&](const void *wt, const void *w, const ActBuf &X, float *Yp, size_t stride, int n, int kd) {
-            int ns = launch_gemm_ws_partial(c, wt, X, Yp, stride, MAX_SPLITS, f.rows, n, kd, KC_GEMM);
+        // wh: the half-precision tiles when this product class runs with one term (more than 16 rows only)
+        auto half = [&](const void *wh, uint32_t cls) { return f.rows > 16 && (c->one_term_mask & cls) ? wh : nullptr; };
+        auto product = [&](const void *wt, const void *w, const void *wh, const ActBuf &X, float *Yp, size_t stride, int n, int kd) {
+            int ns = launch_gemm_ws_partial(c, wt, X, Yp, stride, MAX_SPLITS, f.rows, n, kd, KC_GEMM, nullptr, wh);
             if (!ns) {
                 launch_gemm_ref(c, X.f, w, Yp, f.rows, n, kd, KC_GEMM);
                 ns = 1;
@@ -399,7 +441,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             return ns;
         };
         auto gate_up = [&](const LayerW &L) {
-            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, F, d, KC_GEMM_GATEUP)) {
+            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, F, d, KC_GEMM_GATEUP, half(L.wgu_h, TERM_GATE_UP))) {
                 launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
                 launch_swiglu(c, f.rows);
             }
@@ -419,7 +461,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             }
             if (!nq) {
                 launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
-                nq = product(L.wqkv_t, L.wqkv, c->a, c->qkv, qs, c->d_qkv, d);
+                nq = product(L.wqkv_t, L.wqkv, half(L.wqkv_h, TERM_QKV), c->a, c->qkv, qs, c->d_qkv, d);
             }
             // with few k-splits and few rows the O projection combines the attention partials while it stages them
             const bool defer = fuse_rope && f.rows <= 16 && g.head_dim == 128;
@@ -437,14 +479,14 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
                 }
                 if (!ny) launch_attn_combine(c, f, att_splits);   // more splits than the projection takes: a kernel of its own
             }
-            if (!ny) ny = product(L.wo_t, L.wo, c->o, c->y, ys, d, c->d_q);
+            if (!ny) ny = product(L.wo_t, L.wo, half(L.wo_h, TERM_O), c->o, c->y, ys, d, c->d_q);
             launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
             gate_up(L);
-            ny = product(L.wdown_t, L.wdown, c->h, c->y, ys, d, F);
+            ny = product(L.wdown_t, L.wdown, half(L.wdown_h, TERM_DOWN), c->h, c->y, ys, d, F);
         }
         launch_rmsnorm(c, f.rows, ny, c->final_norm, c->a, c->h_t);
         if (!launch_gemm_ws_argmax(c, c->lm_head_t, c->a, f.keep_logits ? c->logits : nullptr, f.rows, g.vocab, d,
-                                   KC_LMHEAD)) {
+                                   KC_LMHEAD, half(c->lm_head_h, TERM_LM_HEAD))) {
             launch_gemm_ref(c, c->a.f, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
             launch_argmax(c, f.rows);
         }
@@ -816,6 +858,35 @@ extern "C" int wisv_ss_decide_static(wisv_ctx *ctx, int32_t batch, int32_t k, in
                                      int32_t *emitted_token, float *alpha) {
     return ss_decide_common(ctx, true, batch, k, vocab, logits, pending_tokens, draft_tokens, draft_probs, u_accept, u_sample,
                             accepted_len, emitted_token, alpha);
+}
+
+// ------------------------------------------------------------------------------------------ options
+
+extern "C" int wisv_set_option(wisv_ctx *ctx, int32_t option, int64_t value) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (option != WISV_OPT_ONE_TERM_CLASSES) return fail(c, WISV_EINVAL, "unknown option %d", option);
+    if (value < 0 || value > TERM_ALL) return fail(c, WISV_EINVAL, "class mask 0x%llx outside [0, 0x%x]", (long long)value, (int)TERM_ALL);
+    if (value && !c->half_ok)
+        return fail(c, WISV_EUNSUPPORTED, "this ctx has no half-precision weight tiles (fp32 target, at most 16 rows per round, "
+                                          "or a weight beyond the half range)");
+    c->one_term_mask = (uint32_t)value;
+    if (c->graph_exec) {   // a captured round holds the launches of the old setting
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        (void)hipGraphExecDestroy(c->graph_exec);
+        c->graph_exec = nullptr;
+    }
+    c->graph_len_ub = -1;
+    return WISV_OK;
+}
+
+extern "C" int wisv_get_option(wisv_ctx *ctx, int32_t option, int64_t *value) {
+    if (!ctx) return WISV_EINVAL;
+    Ctx *c = ctx;
+    if (option != WISV_OPT_ONE_TERM_CLASSES) return fail(c, WISV_EINVAL, "unknown option %d", option);
+    if (!value) return fail(c, WISV_EINVAL, "value is NULL");
+    *value = c->one_term_mask;
+    return WISV_OK;
 }
 
 // ------------------------------------------------------------------------------------------ state helpers

@@ -46,7 +46,12 @@ __device__ __forceinline__ float wave_max(float v) {
 struct ActBuf {
     float *f;
     bf16_t *hi, *lo;
+    uint16_t *h16;   // the same values as one IEEE half each (null when the ctx never runs the one-term products)
 };
+// nearest-even; magnitudes beyond the largest half saturate instead of becoming infinite
+__device__ __forceinline__ uint16_t f32_to_f16(float f) {
+    return __builtin_bit_cast(uint16_t, (_Float16)__builtin_amdgcn_fmed3f(f, -65504.0f, 65504.0f));
+}
 __device__ __forceinline__ void split2(float v, bf16_t &hi, bf16_t &lo) {
     hi = f32_to_bf16(v);
     lo = f32_to_bf16(v - bf16_to_f32(hi));
@@ -57,6 +62,7 @@ __device__ __forceinline__ void act_store(const ActBuf &a, size_t i, float v) {
     a.f[i] = v;
     a.hi[i] = h;
     a.lo[i] = l;
+    if (a.h16) a.h16[i] = f32_to_f16(v);
 }
 
 // four consecutive elements, i a multiple of 4: one 16-byte and two 8-byte stores
@@ -69,6 +75,9 @@ __device__ __forceinline__ void act_store4(const ActBuf &a, size_t i, float v0, 
     *reinterpret_cast<float4 *>(a.f + i) = make_float4(v0, v1, v2, v3);
     *reinterpret_cast<uint2 *>(a.hi + i) = make_uint2(h[0] | ((unsigned)h[1] << 16), h[2] | ((unsigned)h[3] << 16));
     *reinterpret_cast<uint2 *>(a.lo + i) = make_uint2(l[0] | ((unsigned)l[1] << 16), l[2] | ((unsigned)l[3] << 16));
+    if (a.h16)
+        *reinterpret_cast<uint2 *>(a.h16 + i) = make_uint2(f32_to_f16(v0) | ((unsigned)f32_to_f16(v1) << 16),
+                                                           f32_to_f16(v2) | ((unsigned)f32_to_f16(v3) << 16));
 }
 
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
@@ -81,7 +90,11 @@ enum KernelClass {
 struct LayerW {
     void *attn_norm, *wqkv, *wo, *ffn_norm, *wgu, *wdown;
     void *wqkv_t, *wo_t, *wgu_t, *wdown_t;   // re-tiled copies for the weight-streaming GEMM (bf16 only)
+    void *wqkv_h, *wo_h, *wgu_h, *wdown_h;   // the same tiles as IEEE halves, for the one-term products (or null)
 };
+
+// product classes whose many-rows kernel may take its activations as one half-precision term (wisv_set_option)
+enum { TERM_QKV = 1, TERM_O = 2, TERM_GATE_UP = 4, TERM_DOWN = 8, TERM_LM_HEAD = 16, TERM_ALL = 31 };
 
 struct Ctx {
     wisv_config cfg;
@@ -98,7 +111,9 @@ struct Ctx {
     int d_q, d_kv, d_qkv, rows_max;
 
     // parameters (private copies)
-    void *embed, *lm_head, *final_norm, *lm_head_t;
+    void *embed, *lm_head, *final_norm, *lm_head_t, *lm_head_h;
+    bool half_ok;              // the half-precision weight tiles exist and every weight fits the half range
+    uint32_t one_term_mask;    // TERM_* classes that run with one half-precision term when there are more than 16 rows
     bool ws_ok;          // shapes allow the weight-streaming MFMA GEMM
     std::vector<LayerW> layers;
     void *head_w1, *head_b1, *head_w2, *head_b2;
@@ -214,7 +229,9 @@ constexpr int MAX_SPLITS = 16;
 bool ws_supported(const Ctx *c, int rows, int kd);
 int ws_padded_row_blocks(int n_rows);
 int ws_padded_pair_blocks(int features);
-void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb);
+// overflow != null: the tiles are written as IEEE halves (nearest-even) and *overflow is set to 1 if a weight does not
+// fit the half range
+void launch_retile(Ctx *c, const void *W, int n_rows, int kd, int pair_rows, void *out, int nrb, int32_t *overflow = nullptr);
 // the attention output before its k-splits are combined: o [split][rows][heads][128], m and l [split][rows][heads]
 struct AttnPartials {
     const float *o, *m, *l;
@@ -223,13 +240,15 @@ struct AttnPartials {
 constexpr int WS_PRO_SPLITS = 4;
 // ap != null: X is ignored and the activations are combined from the partials while they are staged (at most 16
 // rows and WS_PRO_SPLITS splits; 0 is returned otherwise)
+// Wh != null: with more than 16 rows the product runs on the half-precision tiles Wh and X.h16 (one MFMA per pair)
 int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, size_t split_stride, int max_splits,
-                           int rows, int n, int kd, int kclass, const AttnPartials *ap = nullptr);
+                           int rows, int n, int kd, int kclass, const AttnPartials *ap = nullptr, const void *Wh = nullptr);
 int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_out, int n_partial, const void *gain,
                             float *Yp, size_t split_stride, int max_splits, int rows, int n, int kd, float *ss, int kclass);
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
-                           int kclass);
-bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass);
+                           int kclass, const void *Wh = nullptr);
+bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass,
+                           const void *Wh = nullptr);
 
 // ---------------------------------------------------------------- split-KV MFMA attention (kernels_attn.hip)
 // true if the shape is served (bf16 cache, head_dim 128, at most 64 query rows per KV head); then c->o holds

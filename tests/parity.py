@@ -33,6 +33,21 @@ TOL_F32 = Tolerance(p_abs=1e-5, logit_rel=1e-5, hidden_rel=1e-5, tie_margin_rel=
 # The stated bounds are 2e-2 on logits and 1e-3 on probabilities; the path is held to far tighter ones.
 TOL_BF16 = Tolerance(p_abs=1e-4, logit_rel=1e-3, hidden_rel=1e-3, tie_margin_rel=2e-2, tie_margin_abs=0.0, tau_margin=1e-4)
 
+# Rounds of more than 16 rows (bound by the matrix cores) feed each activation to the products as ONE half-precision
+# term (2^-12 relative rounding per operand instead of 2^-17).  Bounds derived from measurement at the 8B shape
+# (32 layers): see the table in the design doc; still well inside the stated 2e-2 / 1e-3.
+# Measured with the default classes (gate/up, down, LM head) on configs 3 and 4: logits and h^T <= 2.9e-3 relative,
+# probabilities <= 5.0e-4; with all five classes 4.6e-3 and 5.4e-4.  The probability bound is the stated one.
+TOL_BF16_MANY = Tolerance(p_abs=1e-3, logit_rel=1e-2, hidden_rel=1e-2, tie_margin_rel=2e-2, tie_margin_abs=0.0, tau_margin=1e-3)
+
+
+STATS_LOG = []     # (test tag, statistics) of every parity comparison; conftest prints them at the end of the run
+
+
+def record(tag: str, stats: Dict[str, object]):
+    STATS_LOG.append((tag, dict(stats)))
+    print(f"\n[{tag}] {stats}", flush=True)
+
 
 def to_host_weights(weights: Dict[str, object]) -> Dict[str, object]:
     return {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in weights.items()}

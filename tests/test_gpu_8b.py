@@ -3,12 +3,13 @@ configuration bench.py times.  The KV cache contents and pred_next are seeded sy
 identically for both sides; the oracle recomputes sampled streams in full (every row, every logit), the
 value-free invariants are checked on all streams."""
 import time
+from dataclasses import replace
 
 import numpy as np
 import pytest
 import torch
 
-from parity import OracleSide, TOL_BF16, check_invariants, check_ss_stream as check_stream, compare_stream, row_rel_err, to_host_weights
+from parity import OracleSide, record, TOL_BF16, TOL_BF16_MANY, check_invariants, check_ss_stream as check_stream, compare_stream, row_rel_err, to_host_weights
 from paper_2604_17701_amd import binding
 from wisv_inputs import configs, gen
 from wisv_inputs.configs import PROTO_FH, PROTO_SH
@@ -48,13 +49,19 @@ def _gpu_chain_drafts(ctx, w, pred_next):
     return drafts
 
 
-def _run(w, target8b, sampled, tol=TOL_BF16):
+def _run(w, target8b, sampled, tol=None, one_term=None):
+    """one_term: mask of product classes that take one half-precision term (None: the library's default)."""
     wd, wh = target8b
     t0 = time.time()
     m = w.model
     max_ctx = w.ctx + w.k
     kv = binding.new_kv_cache(m, w.batch, max_ctx, DEV)
     ctx = binding.Context(m, wd, w.batch, max_ctx, w.k, kv_cache=kv)
+    if one_term is not None:
+        ctx.wisv_set_option(binding.WISV_OPT_ONE_TERM_CLASSES, one_term)
+    if tol is None:     # rounds of more than 16 rows run the one-term products unless the mask is empty
+        many = w.m > 16 and ctx.wisv_get_option(binding.WISV_OPT_ONE_TERM_CLASSES) != 0
+        tol = TOL_BF16_MANY if many else TOL_BF16
     side = OracleSide(w, wh)
     pred_next = []
     for b in range(w.batch):
@@ -101,7 +108,7 @@ def _run(w, target8b, sampled, tol=TOL_BF16):
             compare_stream(g, b, o, w.k, tau, tol, stats, logits[rows])
         stats[f"mean_A@{tau}"] = float(np.mean(g["accepted_len"]))
         print(f"[{w.name}] tau={tau} compared at {time.time() - t0:.1f}s", flush=True)
-    print(f"[{w.name}] {stats}", flush=True)
+    record(w.name + ("" if one_term is None else f" one_term={one_term}"), stats)
     ctx.wisv_destroy()
     del kv
     torch.cuda.empty_cache()
@@ -118,6 +125,12 @@ def test_config2_batch1_ctx4096_k8_selective_hidden(target8b):
 
 def test_config3_batch16_ctx2048_k6_tau_sweep(target8b):
     _run(configs.get(3), target8b, sampled=[0, 11])
+
+
+def test_config3_with_two_bf16_terms_everywhere(target8b):
+    """The many-rows kernels in their two-term form (what a ctx falls back to when a weight does not fit a half),
+    held to the tolerance of the memory-bound path."""
+    _run(replace(configs.get(3), taus=(0.5,)), target8b, sampled=[0, 11], tol=TOL_BF16, one_term=0)
 
 
 def test_config4_batch64_ctx8192_k8_mixed_protocols(target8b):
@@ -165,7 +178,7 @@ def test_config1_shape_speculative_sampling_round(target8b):
             check_stream(olog[b], pending[b], tokens[b], q[b], u[b], float(v[b]), int(g["accepted_len"][b]),
                          int(g["correction_token"][b]), g["alpha"][b], 3e-4, stats)
         stats[f"A@{uscale}"] = g["accepted_len"].tolist()
-    print(f"\n[{w.name}] {stats}", flush=True)
+    record(w.name, stats)
     assert stats.get("a_inside_margin", 0) <= 1
     ctx.wisv_destroy()
     del kv

@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from conftest import have_gpu
-from parity import (OracleSide, TOL_BF16, TOL_F32, check_invariants, compare_stream, row_rel_err, to_host_weights)
+from parity import (OracleSide, record, TOL_BF16, TOL_BF16_MANY, TOL_F32, check_invariants, compare_stream, row_rel_err, to_host_weights)
 from paper_2604_17701_amd import binding
 from wisv_inputs import configs, gen
 from wisv_inputs.configs import PROTO_FH, PROTO_SH
@@ -22,13 +22,19 @@ def _ctx(w, weights_dev, max_batch=None, extra_ctx=0):
     return binding.Context(w.model, weights_dev, max_batch or w.batch, w.ctx + w.k + extra_ctx, w.k)
 
 
-def _run_workload(w, tol, kv="prefill", taus=None, keep_logits=True, sampled=None, print_tag=""):
+def _run_workload(w, tol, kv="prefill", taus=None, keep_logits=True, sampled=None, print_tag="", one_term=None):
     """Builds workload w on both sides, runs one round per tau, compares the sampled streams element by
-    element and checks the value-free invariants on all streams."""
+    element and checks the value-free invariants on all streams.  one_term: mask of product classes that take
+    one half-precision term in rounds of more than 16 rows (None: the library's default); tol TOL_BF16 is
+    widened to TOL_BF16_MANY when such products run (round or prefill chunks of more than 16 rows)."""
     dev = torch.device("cuda:0")
     wd = gen.make_weights(w.model, w.seed, dev)
     side = OracleSide(w, to_host_weights(wd))
     ctx = _ctx(w, wd)
+    if one_term is not None:
+        ctx.wisv_set_option(binding.WISV_OPT_ONE_TERM_CLASSES, one_term)
+    if tol is TOL_BF16 and w.m > 16 and ctx.wisv_get_option(binding.WISV_OPT_ONE_TERM_CLASSES) != 0:
+        tol = TOL_BF16_MANY
     sampled = list(range(w.batch)) if sampled is None else sampled
     for b in range(w.batch):
         if kv == "prefill":
@@ -69,7 +75,7 @@ def _run_workload(w, tol, kv="prefill", taus=None, keep_logits=True, sampled=Non
             stats["hidden_rel"] = max(stats.get("hidden_rel", 0.0), herr)
             assert herr <= tol.hidden_rel, f"h^T rel err {herr}"
             compare_stream(g, b, o, w.k, tau, tol, stats, logits[b * w.k:(b + 1) * w.k] if keep_logits else None)
-    print(f"\n[{print_tag or w.name}] {stats}", flush=True)
+    record(print_tag or w.name, stats)
     ctx.wisv_destroy()
     return stats
 
@@ -337,6 +343,32 @@ def test_small_bf16_decoder_kernel_variants(batch, ctx_len, k, kv):
     _run_workload(w, TOL_BF16, kv=kv)
 
 
+@pytest.mark.parametrize("one_term", [0, binding.WISV_TERM_ALL, binding.WISV_TERM_QKV | binding.WISV_TERM_O])
+def test_many_rows_precision_classes(one_term):
+    """72 rows with every product on two bf16 terms (held to the tight tolerance), with all five classes on one
+    half-precision term, and with only the two classes the default leaves on two terms."""
+    protos = tuple(PROTO_FH if b % 2 == 0 else PROTO_SH for b in range(9))
+    w = replace(configs.get(3), model=MID128, batch=9, ctx=40, k=8, protos=protos, kv_source="prefill",
+                name=f"mid128_b9_l40_k8_terms{one_term}", index=18, taus=(0.5,))
+    _run_workload(w, TOL_BF16, kv="prefill", one_term=one_term)
+
+
+def test_precision_option_is_refused_where_it_cannot_apply():
+    dev = torch.device("cuda:0")
+    wd = gen.make_weights(W0.model, W0.seed, dev)
+    ctx = _ctx(W0, wd)                                   # fp32 target: no half-precision tiles
+    assert ctx.wisv_get_option(binding.WISV_OPT_ONE_TERM_CLASSES) == 0
+    with pytest.raises(binding.WisvError) as e:
+        ctx.wisv_set_option(binding.WISV_OPT_ONE_TERM_CLASSES, binding.WISV_TERM_DOWN)
+    assert e.value.code == binding.WISV_EUNSUPPORTED
+    with pytest.raises(binding.WisvError):
+        ctx.wisv_set_option(binding.WISV_OPT_ONE_TERM_CLASSES, 64)
+    with pytest.raises(binding.WisvError):
+        ctx.wisv_set_option(77, 0)
+    ctx.wisv_set_option(binding.WISV_OPT_ONE_TERM_CLASSES, 0)
+    ctx.wisv_destroy()
+
+
 def test_small_bf16_decoder_synthetic_kv():
     w = replace(configs.get(2), model=replace(MID, head_dim=128, n_heads=4, n_kv_heads=1), batch=2, ctx=1100, k=8,
                 protos=(PROTO_SH, PROTO_FH), name="mid_bf16_synthkv", index=8)
@@ -421,5 +453,5 @@ def test_mixed_context_lengths_in_one_round(lengths, k):
         stats["logit_rel"] = max(stats.get("logit_rel", 0.0), err)
         assert err <= TOL_BF16.logit_rel, (b, err)
         compare_stream(g, b, o, k, 0.5, TOL_BF16, stats, logits[rows])
-    print(f"\n[{base.name}] {stats}", flush=True)
+    record(base.name, stats)
     ctx.wisv_destroy()

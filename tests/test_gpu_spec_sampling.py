@@ -10,7 +10,7 @@ import pytest
 import torch
 
 from oracle import spec_sampling as ss
-from parity import OracleSide, check_ss_stream as check_stream, to_host_weights
+from parity import OracleSide, record, check_ss_stream as check_stream, to_host_weights
 from paper_2604_17701_amd import binding
 from wisv_inputs import configs, gen
 
@@ -68,7 +68,7 @@ def _decide_case(ctx, seed, batch, k, vocab, scale, tol=2e-6):
         s = slice(b * k, (b + 1) * k)
         check_stream(logits[s], int(pending[b]), tokens[s], q[s], u[s], float(v[b]), int(alen[b]), int(tok[b]),
                      alpha[b], tol, stats)
-    print(f"\n[ss_decide b={batch} k={k} V={vocab}] {stats} A={np.bincount(alen, minlength=k + 1)}", flush=True)
+    record(f"ss_decide b={batch} k={k} V={vocab}", {**stats, "A_histogram": np.bincount(alen, minlength=k + 1).tolist()})
     assert stats.get("a_inside_margin", 0) <= max(1, batch // 10)
     if stats.get("tokens", 0) >= 8:
         assert stats["tokens_equal"] >= 0.85 * stats["tokens"]
@@ -140,7 +140,7 @@ def test_ss_round_tiny_target_chain_of_rounds():
             length[b] += a
             pending[b] = tok
             assert ctx.wisv_get_state(b) == (length[b], pending[b])
-    print(f"\n[ss_round tiny] {stats}", flush=True)
+    record("ss_round tiny", stats)
     assert stats.get("a_inside_margin", 0) == 0
     ctx.wisv_destroy()
 
@@ -212,6 +212,6 @@ def test_ss_round_bf16_decoder_many_rows_odd_vocabulary():
         check_stream(olog[b], pending[b], tokens[b], q[b], u[b], float(v[b]), int(g["accepted_len"][b]),
                      int(g["correction_token"][b]), g["alpha"][b], 1e-3, stats)
     stats["A"] = g["accepted_len"].tolist()
-    print(f"\n[ss_round bf16 25 rows] {stats}", flush=True)
+    record("ss_round bf16 25 rows", stats)
     assert stats.get("a_inside_margin", 0) <= 1
     ctx.wisv_destroy()
