@@ -205,6 +205,8 @@ def main():
     ap.add_argument("--loop", type=int, default=0,
                     help="also run N consecutive committed rounds per stream with a synthetic drafter and report the "
                          "average accepted length (not part of the timed steps)")
+    ap.add_argument("--shape", default=None,
+                    help="BATCH,CONTEXT,K: the chosen config's recipe at another batch / cached length / block size")
     ap.add_argument("--one-term", type=int, default=None,
                     help="mask of product classes (1 QKV, 2 O, 4 gate/up, 8 down, 16 LM head) that take their activations as one "
                          "half-precision term in rounds of more than 16 rows (default: the library's, all five)")
@@ -224,6 +226,11 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU: the verify round has no CPU implementation")
     w = configs.get(a.config)
+    if a.shape:
+        from dataclasses import replace
+        b_, l_, k_ = (int(x) for x in a.shape.split(","))
+        w = replace(w, name=f"{w.name}_as_b{b_}_l{l_}_k{k_}", batch=b_, ctx=l_, k=k_,
+                    protos=tuple(w.protos[i % len(w.protos)] for i in range(b_)))
     dev = "cuda:0"
     t0 = time.time()
     wd = gen.make_weights(w.model, w.seed if a.config == 0 else configs.get(1).seed, dev)

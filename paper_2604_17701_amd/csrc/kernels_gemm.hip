@@ -805,6 +805,11 @@ static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
 enum { MM_NARROW = 0, MM_NORMAL = 1, MM_WIDE = 2, MM_KSLICE = 3 };   // 2 x 2, 4 x 2, 8 x 1 waves for more than 64 rows
 static int mm_layout(int rows, int nrb, int nkt, bool can_split, int max_splits) {
     if (!can_split && rows <= 64 && (nrb + 8 * MM_RB - 1) / (8 * MM_RB) < 200) return MM_KSLICE;
+    // Products with k-splits over at most 128 rows: every slice costs rows x n floats to write and to read back, so
+    // narrow workgroups that need fewer splits to fill the chip win: k-slice workgroups up to 64 rows (32 rows at
+    // the 8B shape: round 5.07 -> 4.63 ms, 64 rows: 5.89 -> 5.59), 2 x 2 waves beyond (96 rows: 7.10 -> 6.63 ms).
+    if (can_split && rows <= 64) return MM_KSLICE;
+    if (can_split && rows <= 128) return MM_NARROW;
     if (rows <= 64) return MM_NORMAL;
     const int tiles = (rows + 127) / 128;
     const int base8 = ((nrb + 8 * MM_RB - 1) / (8 * MM_RB)) * tiles, base4 = ((nrb + 4 * MM_RB - 1) / (4 * MM_RB)) * tiles;
@@ -815,6 +820,10 @@ static int mm_layout(int rows, int nrb, int nkt, bool can_split, int max_splits)
 
 // returns the number of row tiles and of row-blocks a workgroup covers
 static int mm_shape(int rows, int layout, int *rb_per_wg) {
+    if (layout == MM_KSLICE) {
+        *rb_per_wg = 2 * MM_RB;
+        return 1;
+    }
     *rb_per_wg = (rows <= 64 || layout == MM_WIDE ? 8 : layout == MM_NORMAL ? 4 : 2) * MM_RB;
     return rows <= 64 ? 1 : (rows + 127) / 128;
 }
@@ -823,7 +832,9 @@ static int mm_shape(int rows, int layout, int *rb_per_wg) {
 template <int EPI, int NPL> static bool launch_ws_many_t(Ctx *c, GemmArgs &g, int splits, int layout) {
     if (layout == MM_KSLICE) {   // 2 row-block groups x 4 k-slices
         if (g.M <= 32) return launch_mm_t<1, 1, 8, 4, 4, 4, EPI, NPL>(c, g, splits);
-        return launch_mm_t<2, 1, 8, 4, 4, 4, EPI, NPL>(c, g, splits);
+        if (g.M <= 64) return launch_mm_t<2, 1, 8, 4, 4, 4, EPI, NPL>(c, g, splits);
+        if (g.M <= 96) return launch_mm_t<3, 1, 8, 4, 4, 4, EPI, NPL>(c, g, splits);
+        return launch_mm_t<4, 1, 8, 4, 4, 4, EPI, NPL>(c, g, splits);
     }
     if (g.M <= 32) {   // one row tile, one plane: chunks of four k-tiles give every wave an operand to stage
         if (NPL == 1) return launch_mm_t<1, 1, 8, 1, 4, 4, EPI, NPL>(c, g, splits);
