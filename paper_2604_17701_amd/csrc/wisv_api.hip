@@ -370,7 +370,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     }
     CREATE_TRY(dalloc(c, &c->gu, (size_t)R * 2 * F));
     CREATE_TRY(dalloc(c, &c->h_t, (size_t)R * d));
-    CREATE_TRY(dalloc(c, &c->hu, (size_t)MAX_SPLITS * R * g.d_head_hidden));
+    CREATE_TRY(dalloc(c, &c->hu, (size_t)((g.d_head_hidden + 15) / 16) * R));   // the head's partial sums [row-block][row]
     auto act_alloc = [&](ActBuf *a, size_t n, bool half) -> hipError_t {
         hipError_t e = dalloc(c, &a->f, n);
         if (e == hipSuccess) e = dalloc(c, &a->hi, n);
@@ -382,7 +382,6 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     CREATE_TRY(act_alloc(&c->a, (size_t)R * d, c->half_ok));
     CREATE_TRY(act_alloc(&c->o, (size_t)R * c->d_q, c->half_ok));
     CREATE_TRY(act_alloc(&c->h, (size_t)R * F, c->half_ok));
-    CREATE_TRY(act_alloc(&c->z, (size_t)R * c->din_pad, false));
     CREATE_TRY(dalloc(c, &c->q, (size_t)R * c->d_q));
     {
         // split-KV attention partials: as many splits as fit 64 MiB, at most 64

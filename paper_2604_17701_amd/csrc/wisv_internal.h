@@ -149,8 +149,8 @@ struct Ctx {
     float *cand_val;
     int32_t *cand_idx;
     float *q;                     // rotated queries [rows][d_q]
-    ActBuf a, o, h, z;            // normalised activations, attention output, SwiGLU output, head input
-    float *hu;                    // decision head: first-layer slices
+    ActBuf a, o, h;               // normalised activations, attention output, SwiGLU output
+    float *hu;                    // decision head: second-layer partial sums [row-block of hidden units][row]
     float *att_o, *att_m, *att_l; // split-KV attention partials: [split][rows][heads][head_dim], [split][rows][heads]
     int att_max_splits;
     size_t logits_rows;
