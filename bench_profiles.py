@@ -1,12 +1,13 @@
-"""Turns rocprofv3 CSV output of a bench.py run into the short text summaries kept under profiles/.
+"""The rocprofv3 side of bench.py: turns rocprofv3 CSV output of a bench.py run into the short text summaries kept
+under profiles/, and reads those summaries back for bench.py's roofline line.
 
-    python -m paper_2604_17701_amd.profile_summary kernels <kernel_stats.csv> <out.txt> "<command>"
-    python -m paper_2604_17701_amd.profile_summary traffic <fetch counter_collection.csv> <write counter_collection.csv> <out.txt> "<commands>"
-    python -m paper_2604_17701_amd.profile_summary counters <counter_collection.csv> <out.txt> "<command>"
+    python bench_profiles.py kernels <kernel_stats.csv> <out.txt> "<command>"
+    python bench_profiles.py traffic <fetch counter_collection.csv> <write counter_collection.csv> <out.txt> "<commands>"
+    python bench_profiles.py counters <counter_collection.csv> <out.txt> "<command>"
 
 The traffic summary scales FETCH_SIZE / WRITE_SIZE by what the same counters read for the library's plain
-1 GiB copy kernel in the same run, and records a hash of the kernel sources so that bench.py can tell whether
-the figures still describe the kernels it runs.
+1 GiB copy kernel in the same run, and every summary records a hash of the kernel sources so that bench.py can tell
+whether the figures still describe the kernels it runs.
 """
 from __future__ import annotations
 
@@ -17,13 +18,14 @@ import hashlib
 import os
 import sys
 
-PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(ROOT, "paper_2604_17701_amd", "csrc")
 COPY_BYTES = float(1 << 30)
 
 
 def source_hash() -> str:
     h = hashlib.sha256()
-    for p in sorted(glob.glob(os.path.join(PKG, "csrc", "*"))):
+    for p in sorted(glob.glob(os.path.join(CSRC, "*"))):
         with open(p, "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
@@ -47,6 +49,7 @@ def kernels(stats_csv: str, out: str, command: str):
                      f"{100 * float(r['TotalDurationNs']) / total:5.1f} % of library kernel time")
     with open(out, "w") as f:
         f.write(f"# rocprofv3 --kernel-trace --stats summary (library kernels only)\n# command: {command}\n")
+        f.write(f"source_sha256 {source_hash()}\n")
         f.write("\n".join(lines) + "\n")
 
 
@@ -135,6 +138,30 @@ def template_args(kernel: str):
         return kernel, []
     base, rest = kernel.split("<", 1)
     return base, [a.strip() for a in rest.rstrip(">").split(",")]
+
+
+def read_hash(path: str):
+    """The source hash a summary was taken at (None for a summary without one)."""
+    with open(path) as f:
+        for line in f:
+            if line.startswith("source_sha256"):
+                return line.split()[1]
+    return None
+
+
+# position of the epilogue in the template arguments of the two GEMM kernels, and which class an epilogue means
+_EPI_ARG = {"k_gemm_ws": 6, "k_gemm_mm": 7}
+_EPI_CLASS = {"0": "gemm_qkv_o_down", "1": "gemm_gate_up", "2": "lm_head"}
+
+
+def kernel_class(kernel: str):
+    """bench.py's kernel class of a (shortened) kernel name, or None."""
+    base, args = template_args(kernel)
+    if base == "k_attn_mfma":
+        return "attention"
+    if base in _EPI_ARG and len(args) > _EPI_ARG[base]:
+        return _EPI_CLASS.get(args[_EPI_ARG[base]])
+    return None
 
 
 if __name__ == "__main__":

@@ -63,7 +63,11 @@ typedef enum { WISV_ACT_SILU = 0, WISV_ACT_RELU = 1 /* eq. mlp_form */ } wisv_ac
 /* wisv_round_in.flags */
 #define WISV_FLAG_GATE_ALL 1u    /* the head gates every position, not only S (needs h^D everywhere) */
 #define WISV_FLAG_NO_COMMIT 2u   /* leave kv_len / pred_next of the streams unchanged */
-#define WISV_FLAG_DEVICE_IO 4u   /* all round_in / round_out pointers are device pointers; enqueue only */
+#define WISV_FLAG_DEVICE_IO 4u   /* all round_in / round_out pointers are device pointers; enqueue only.  The host
+                                    cannot see which slots such a round uses or how much it accepted: after a committing
+                                    device-I/O round it assumes every slot grew by k, and refuses further rounds with
+                                    WISV_ESTATE once that bound reaches max_ctx.  wisv_get_state(slot) reads the true
+                                    length back and resets the bound of that slot. */
 #define WISV_FLAG_KEEP_LOGITS 8u /* also materialise fp32 logits for wisv_debug_copy (debug, slow) */
 /* The selective-hidden protocol in two calls (Alg. 1: Verify, Localize, RequestHidden(S), then the head on the
  * uploaded rows; Sec. III-B).  VERIFY_ONLY runs the target forward and the localisation: target_argmax and
@@ -282,34 +286,8 @@ int wisv_kv_import(wisv_ctx *ctx, int32_t stream_id, int32_t layer, const void *
 int wisv_kv_export(wisv_ctx *ctx, int32_t stream_id, int32_t layer, void *host_k, void *host_v,
                    int32_t len);
 
-/* --- diagnostics ----------------------------------------------------------------------------- */
-
-typedef enum {
-    WISV_DBG_HIDDEN = 0, /* float [batch*k, d_model]: h^T of the last round */
-    WISV_DBG_LOGITS = 1  /* float [batch*k, vocab]: logits of the last round run with WISV_FLAG_KEEP_LOGITS */
-} wisv_debug_what;
-
-/* Copies a diagnostic buffer of the last round to host memory (synchronises). */
-int wisv_debug_copy(wisv_ctx *ctx, int32_t what, void *host_dst, size_t bytes);
-
-/* Duration in milliseconds of the GPU work of the last wisv_verify_round, measured with HIP events
- * recorded on the ctx's stream around the round's kernels (waits for the round to finish). */
-int wisv_last_round_ms(wisv_ctx *ctx, float *ms);
-
-/* Per-kernel timing.  While enabled, every kernel launch of a round is bracketed by a HIP event pair
- * on the ctx's stream.  wisv_profile_collect() waits for the stream and adds the elapsed times of the
- * launches since the last collect to per-class totals; wisv_profile_read() returns one class's name
- * (static string), accumulated milliseconds and launch count.  Enabling or disabling resets the totals.
- * The class "event_pair_overhead" times one empty event pair per round: what the bracketing itself adds.
- * kclass runs from 0 until wisv_profile_read() returns WISV_EINVAL. */
-int wisv_profile_enable(wisv_ctx *ctx, int32_t on);
-int wisv_profile_collect(wisv_ctx *ctx);
-int wisv_profile_read(wisv_ctx *ctx, int32_t kclass, const char **name, double *total_ms, int64_t *launches);
-
-/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned
- * device memory) on the ctx's stream: a kernel of known traffic, used to calibrate hardware memory counters
- * when profiling the round. */
-int wisv_calibration_copy(wisv_ctx *ctx, void *dst, const void *src, size_t bytes);
+/* Diagnostics and measurement helpers (debug copies, per-kernel timing, the counter-calibration copy) are declared
+ * in wisv_diag.h. */
 
 /* Message of the last error on this ctx ("" if none).  Never NULL. */
 const char *wisv_last_error(const wisv_ctx *ctx);

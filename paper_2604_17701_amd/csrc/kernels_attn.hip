@@ -466,13 +466,8 @@ __global__ void k_attn_combine(const float *__restrict__ po, const float *__rest
 template <int NQ, int NW, bool FUSE> static bool launch_nq(Ctx *c, const AttnArgs &a, dim3 grid) {
     // the merge area at the end of the kernel, which also holds the parked query operands before that
     const size_t lds = std::max((size_t)NW * NQ * (2 * 16 * 4 + 8 * 64 * 16), (size_t)NQ * 8 * 1024);
-    static bool opted_in = false;
-    if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_mfma<NQ, NW, FUSE>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return false;
-        opted_in = true;
-    }
+    static bool allowed[MAX_DEVICES];
+    if (lds > 64 * 1024 && !allow_big_lds(c, reinterpret_cast<const void *>(&k_attn_mfma<NQ, NW, FUSE>), allowed)) return false;
     hipLaunchKernelGGL((k_attn_mfma<NQ, NW, FUSE>), grid, dim3(64 * NW), lds, c->stream, a);
     return true;
 }

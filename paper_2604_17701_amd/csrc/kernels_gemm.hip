@@ -757,13 +757,9 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
     }
     if (lds > 150 * 1024) return false;
     g.kcw = kcw;
-    static bool opted_in = false;     // per instantiation
-    if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<NT, RB, WR, WK, U, PRO, EPI>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return false;
-        opted_in = true;
-    }
+    static bool allowed[MAX_DEVICES];     // per instantiation
+    if (lds > 64 * 1024 && !allow_big_lds(c, reinterpret_cast<const void *>(&k_gemm_ws<NT, RB, WR, WK, U, PRO, EPI>), allowed))
+        return false;
     dim3 grid((g.nrb / RB + WR - 1) / WR, splits, (g.M + 16 * NT - 1) / (16 * NT));
     hipLaunchKernelGGL((k_gemm_ws<NT, RB, WR, WK, U, PRO, EPI>), grid, dim3(64 * WR * WK), lds, c->stream, g);
     return true;
@@ -780,13 +776,10 @@ static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
     g.gs = splits;
     // two buffers, two planes, 2 operands per (k-tile, row tile); or the k-slice reduction: one accumulator set per tile group
     const size_t lds = std::max((size_t)2 * NPL * KC * NTW * 2 * 1024, WK > 1 ? (size_t)WN * WM * MM_RP * NT * 4096 : (size_t)0);
-    static bool opted_in = false;     // per instantiation
-    if (lds > 64 * 1024 && !opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return false;
-        opted_in = true;
-    }
+    static bool allowed[MAX_DEVICES];     // per instantiation
+    if (lds > 64 * 1024 &&
+        !allow_big_lds(c, reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL>), allowed))
+        return false;
     const unsigned grid = (unsigned)((g.gx * g.gs + 7) / 8 * 8 * g.gz);
     hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
     return true;

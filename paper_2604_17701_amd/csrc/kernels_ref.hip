@@ -294,7 +294,16 @@ void launch_attn_ref(Ctx *c, const Fwd &f, int layer) {
     ProfScope ps(c, KC_ATTN);
     const wisv_config &g = c->cfg;
     const size_t slot_stride = (size_t)2 * g.n_kv_heads * c->ctx_pad * g.head_dim;
+    // the kernel keeps every visible score in LDS: contexts beyond what a workgroup may hold are not served
     const size_t lds = sizeof(float) * (g.head_dim + 260 + f.max_len_ub);
+    static bool allowed_bf16[MAX_DEVICES], allowed_f32[MAX_DEVICES];
+    const void *kern = c->bf16 ? reinterpret_cast<const void *>(&k_attn_ref<bf16_t, float>) : reinterpret_cast<const void *>(&k_attn_ref<float, float>);
+    if (lds > 160 * 1024 || (lds > 64 * 1024 && !allow_big_lds(c, kern, c->bf16 ? allowed_bf16 : allowed_f32))) {
+        c->launch_failed = true;
+        c->launch_err = "the generic attention kernel holds one score per visible position in LDS: a context of " +
+                        std::to_string(f.max_len_ub) + " positions does not fit (this shape is not served by the MFMA attention kernel)";
+        return;
+    }
     dim3 grid(f.rows, g.n_heads);
     void *kvl = kv_ptr(c, layer, 0, 0);
     if (c->bf16)

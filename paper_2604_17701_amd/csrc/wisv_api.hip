@@ -163,6 +163,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     c->ss_ws = nullptr;
     c->d_ss_q = c->d_ss_u = c->d_ss_v = nullptr;
     c->last_rows = 0;
+    c->launch_failed = false;
     memset(c->prof_ms, 0, sizeof c->prof_ms);
     memset(c->prof_n, 0, sizeof c->prof_n);
     c->h_len_ub.assign(config->max_batch, 0);
@@ -623,9 +624,33 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
     // few hundred launches.  Positions are read from device state, so a replay stays valid while the upper
     // bound of the cached lengths (which sizes the attention launch) is unchanged.
     const bool graphable = dev_io && !c->profiling;
-    const bool same_call = graphable && c->graph_len_ub == len_ub && !memcmp(&c->graph_in, in, sizeof *in) &&
-                           !memcmp(&c->graph_out, out, sizeof *out);
+    auto same_in = [](const wisv_round_in &x, const wisv_round_in &y) {
+        return x.batch == y.batch && x.k == y.k && x.stream_ids == y.stream_ids && x.draft_tokens == y.draft_tokens &&
+               x.proto == y.proto && x.hd == y.hd && x.hd_row == y.hd_row && x.n_hd == y.n_hd && x.csi == y.csi &&
+               x.tau == y.tau && x.flags == y.flags;
+    };
+    auto same_out = [](const wisv_round_out &x, const wisv_round_out &y) {
+        return x.accepted_len == y.accepted_len && x.correction_token == y.correction_token && x.p_accept == y.p_accept &&
+               x.target_argmax == y.target_argmax && x.mismatch_mask == y.mismatch_mask && x.status == y.status;
+    };
+    const bool same_call = graphable && c->graph_len_ub == len_ub && same_in(c->graph_in, *in) && same_out(c->graph_out, *out);
     HIP_TRY(c, hipEventRecord(c->ev_round[0], c->stream));
+    c->launch_failed = false;
+    auto enqueue_round = [&]() -> hipError_t {
+        { ProfScope empty(c, KC_EMPTY); }   // an event pair with nothing in between: what the bracketing itself costs
+        if (!decide_only) enqueue_forward(c, f);   // else: h^T, the greedy tokens and the appended K/V are still there
+        if (c->launch_failed) return hipSuccess;   // a step was not served: nothing may be decided or committed from the rest
+        if (verify_only) {
+            // localisation only: no hidden state counts as uploaded, nothing is committed
+            din.n_hd = 0;
+            din.hd_row = c->d_hd_row;
+            hipError_t e = hipMemsetAsync(c->d_hd_row, 0xff, (size_t)R * 4, c->stream);   // every row: -1, not uploaded
+            if (e != hipSuccess) return e;
+            din.flags |= WISV_FLAG_NO_COMMIT;
+        }
+        launch_head_decide(c, f, din, dout);
+        return hipSuccess;
+    };
     if (same_call && c->graph_exec) {
         HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->stream));
     } else {
@@ -634,34 +659,38 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
             (void)hipGraphExecDestroy(c->graph_exec);
             c->graph_exec = nullptr;
         }
-        const bool capture = same_call;   // the first call of a kind always runs eagerly (one-time kernel attribute set-up)
-        if (capture) HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-        { ProfScope empty(c, KC_EMPTY); }   // an event pair with nothing in between: what the bracketing itself costs
-        if (!decide_only) enqueue_forward(c, f);   // else: h^T, the greedy tokens and the appended K/V are still there
-        if (verify_only) {
-            // localisation only: no hidden state counts as uploaded, nothing is committed
-            din.n_hd = 0;
-            din.hd_row = c->d_hd_row;
-            HIP_TRY(c, hipMemsetAsync(c->d_hd_row, 0xff, (size_t)R * 4, c->stream));   // every row: -1, not uploaded
-            din.flags |= WISV_FLAG_NO_COMMIT;
-        }
-        launch_head_decide(c, f, din, dout);
-        if (capture) {
-            hipGraph_t graph = nullptr;
-            HIP_TRY(c, hipStreamEndCapture(c->stream, &graph));
-            hipError_t e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
-            (void)hipGraphDestroy(graph);
-            if (e != hipSuccess) {
-                c->graph_exec = nullptr;
-                return fail(c, WISV_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
+        bool captured = false;
+        if (same_call) {   // the first call of a kind always runs eagerly (one-time kernel attribute set-up)
+            // Capture, instantiate, launch.  Whatever fails, the capture is ended and its graph dropped, and the round
+            // is enqueued eagerly instead: a failed capture must not leave the (possibly borrowed) stream capturing.
+            if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal) == hipSuccess) {
+                const hipError_t e_enq = enqueue_round();
+                hipGraph_t graph = nullptr;
+                const hipError_t e_end = hipStreamEndCapture(c->stream, &graph);
+                hipGraphExec_t exec = nullptr;
+                if (e_enq == hipSuccess && e_end == hipSuccess && graph && !c->launch_failed &&
+                    hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess) {
+                    if (hipGraphLaunch(exec, c->stream) == hipSuccess) {
+                        c->graph_exec = exec;
+                        captured = true;
+                    } else {
+                        (void)hipGraphExecDestroy(exec);
+                    }
+                }
+                if (graph) (void)hipGraphDestroy(graph);
+                (void)hipGetLastError();   // a capture error is not this round's error: the eager path decides
             }
-            HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->stream));
         }
+        if (!captured && !c->launch_failed) HIP_TRY(c, enqueue_round());
         if (graphable) {
-            memcpy(&c->graph_in, in, sizeof *in);     // bytewise, padding included: the key is compared with memcmp
-            memcpy(&c->graph_out, out, sizeof *out);
+            c->graph_in = *in;        // compared member by member (struct padding is not part of the key)
+            c->graph_out = *out;
             c->graph_len_ub = len_ub;
         }
+    }
+    if (c->launch_failed) {
+        c->graph_len_ub = -1;
+        return fail(c, WISV_EUNSUPPORTED, "%s", c->launch_err.c_str());
     }
     HIP_TRY(c, hipEventRecord(c->ev_round[1], c->stream));
     HIP_TRY(c, hipGetLastError());
@@ -779,7 +808,9 @@ extern "C" int wisv_ss_verify_round(wisv_ctx *ctx, const wisv_ss_in *in, wisv_ss
 
     HIP_TRY(c, hipEventRecord(c->ev_round[0], c->stream));
     { ProfScope empty(c, KC_EMPTY); }
+    c->launch_failed = false;
     enqueue_forward(c, f);
+    if (c->launch_failed) return fail(c, WISV_EUNSUPPORTED, "%s", c->launch_err.c_str());
     launch_ss(c, a);
     HIP_TRY(c, hipEventRecord(c->ev_round[1], c->stream));
     HIP_TRY(c, hipGetLastError());
@@ -950,9 +981,14 @@ extern "C" int wisv_prefill(wisv_ctx *ctx, int32_t stream_id, const int32_t *tok
         f.tokens = c->d_tokens;
         f.keep_logits = false;
         f.max_len_ub = len + c0 + rows;
+        c->launch_failed = false;
         enqueue_forward(c, f);
+        // the slot's state moves only past chunks whose every kernel was launched
+        if (c->launch_failed) return fail(c, WISV_EUNSUPPORTED, "%s", c->launch_err.c_str());
+        HIP_TRY(c, hipGetLastError());
         launch_set_pred_next(c, stream_id, rows - 1, len + c0 + rows);
         HIP_TRY(c, hipStreamSynchronize(c->stream));   // d_tokens is reused by the next chunk
+        c->h_len_ub[stream_id] = len + c0 + rows;
     }
     HIP_TRY(c, hipGetLastError());
     c->h_len_ub[stream_id] = len + n;

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "wisv.h"
+#include "wisv_diag.h"
 
 namespace wisv {
 
@@ -171,6 +172,10 @@ struct Ctx {
     int pending_batch, pending_k;
     std::vector<int32_t> pending_ids, pending_tokens;
 
+    // a launcher that cannot serve a shape mid-forward (no kernel fits) says so here; the entry point reports it
+    bool launch_failed;
+    std::string launch_err;
+
     std::string err;
     std::vector<void *> owned;    // device allocations to free
 };
@@ -263,6 +268,18 @@ void launch_attn_combine(Ctx *c, const Fwd &f, int n_splits);
 // true if launch_attn_mfma(.., n_partial > 0) will do RoPE and the cache append itself from the k-split slices of
 // the QKV product (then launch_rope_append must not run)
 bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f);
+
+// A kernel that wants more than 64 KiB of dynamic LDS must be allowed to once per device.  `done` is the caller's
+// per-kernel table (one flag per device): a cache of an idempotent call, not state that results depend on.
+constexpr int MAX_DEVICES = 64;
+inline bool allow_big_lds(const Ctx *c, const void *kernel, bool (&done)[MAX_DEVICES]) {
+    const int dev = c->cfg.device_id;
+    if (dev < 0 || dev >= MAX_DEVICES) return false;
+    if (done[dev]) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return false;
+    done[dev] = true;
+    return true;
+}
 
 // records the event pair of one launch when profiling is on
 struct ProfScope {

@@ -13,8 +13,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    with open(os.path.join(ROOT, "include", "wisv.h")) as f:
-        text = f.read()
+    text = ""
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if name.endswith(".h"):
+            with open(os.path.join(ROOT, "include", name)) as f:
+                text += f.read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(wisv_[a-z_0-9]+)\s*\(", text)))
 
@@ -107,17 +110,23 @@ def test_bench_refuses_more_than_one_gpu():
 
 def test_profile_summaries_parse_and_name_the_kernels_bench_looks_for():
     """The committed rocprofv3 summaries are what bench.py reads its traffic and duration figures from: they must
-    parse, and hold the kernel classes of the two workloads bench.py reports them for."""
-    from paper_2604_17701_amd import profile_summary as ps
+    parse, carry the hash of the sources they were taken at, and hold the kernel classes bench.py reports for each
+    of the four 8B-shaped workloads."""
+    import bench_profiles as ps
     prof = os.path.join(ROOT, "profiles")
-    for workload, base, epi in (("cfg1_8b_b1_l512_k4", "k_gemm_ws", "1"), ("cfg4_8b_b64_l8192_k8_mixed", "k_attn_mfma", None)):
+    for index in (1, 2, 3, 4):
+        workload = configs.get(index).name
         sha, table = ps.read_traffic(os.path.join(prof, f"{workload}_hbm_traffic.txt"))
-        kern = ps.read_kernels(os.path.join(prof, f"{workload}_kernel_stats.txt"))
-        assert sha and len(sha) == 16
+        stats = os.path.join(prof, f"{workload}_kernel_stats.txt")
+        kern = ps.read_kernels(stats)
+        assert sha and len(sha) == 16 and ps.read_hash(stats) == sha, workload
         for names in (table, kern):
-            hits = [n for n in names if ps.template_args(n)[0] == base and (epi is None or ps.template_args(n)[1][-1] == epi)]
-            assert hits, (workload, base)
-        n, fetch, write = table[hits[0]] if hits[0] in table else next(iter(table.values()))
-        assert n > 0 and fetch > 0
-    assert ps.template_args("k_gemm_ws<1, 1, 7, 1, 16, false, 1>") == ("k_gemm_ws", ["1", "1", "7", "1", "16", "false", "1"])
-    assert ps.template_args("k_decide") == ("k_decide", [])
+            classes = {ps.kernel_class(n) for n in names}
+            assert {"gemm_gate_up", "gemm_qkv_o_down", "lm_head", "attention"} <= classes, (workload, classes)
+        for n, fetch, write in table.values():
+            assert n > 0 and fetch >= 0 and write >= 0
+    assert ps.template_args("k_gemm_ws<1, 1, 7, 1, 16, 0, 1>") == ("k_gemm_ws", ["1", "1", "7", "1", "16", "0", "1"])
+    assert ps.kernel_class("k_gemm_ws<1, 1, 7, 1, 16, 0, 1>") == "gemm_gate_up"
+    assert ps.kernel_class("k_gemm_mm<4, 1, 8, 1, 2, 2, 2, 2, 1>") == "lm_head"
+    assert ps.kernel_class("k_attn_mfma<1, 8, true>") == "attention"
+    assert ps.template_args("k_decide") == ("k_decide", []) and ps.kernel_class("k_decide") is None

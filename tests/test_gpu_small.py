@@ -308,6 +308,30 @@ def test_round_argument_errors_leave_outputs_untouched():
     ctx.wisv_destroy()
 
 
+def test_generic_attention_refuses_contexts_its_workgroup_cannot_hold():
+    """The generic attention kernel (float targets, unusual head sizes) keeps one score per visible position in LDS.
+    Up to a CU's LDS it runs (beyond 64 KiB after opting in); a longer context is refused with WISV_EUNSUPPORTED and
+    nothing is decided or committed - it must not be launched with more LDS than exists."""
+    dev = torch.device("cuda:0")
+    wd = gen.make_weights(W0.model, W0.seed, dev)
+    ctx = binding.Context(W0.model, wd, 1, 50000, W0.k)
+    k, csi, hd = W0.k, gen.csi_features(W0), gen.draft_hidden(W0, 0)
+    draft = gen.build_drafts(W0, 0, None)
+    ctx.wisv_set_state(0, 20000, 5)                      # 80 KiB of scores: needs the opt-in, then runs
+    g = ctx.wisv_verify_round([0], draft, [PROTO_FH], hd, None, csi, [0.5], k, binding.WISV_FLAG_NO_COMMIT)
+    check_invariants(g, draft, k)
+    ctx.wisv_set_state(0, 45000, 5)                      # 180 KiB: more than a workgroup can have
+    with pytest.raises(binding.WisvError) as e:
+        ctx.wisv_verify_round([0], draft, [PROTO_FH], hd, None, csi, [0.5], k, 0)
+    assert e.value.code == binding.WISV_EUNSUPPORTED and "LDS" in str(e.value)
+    assert ctx.wisv_get_state(0) == (45000, 5)
+    with pytest.raises(binding.WisvError) as e:          # prefill takes the same kernels: the state stays where it was
+        ctx.wisv_prefill(0, np.arange(8) % W0.model.vocab)
+    assert e.value.code == binding.WISV_EUNSUPPORTED
+    assert ctx.wisv_get_state(0) == (45000, 5)
+    ctx.wisv_destroy()
+
+
 # ---------------------------------------------------------------- small bf16 decoders (GQA, ragged sizes)
 
 MID = replace(configs.LLAMA8B, n_layers=3, d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, d_ff=1376, vocab=5003,
