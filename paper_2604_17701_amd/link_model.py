@@ -92,6 +92,18 @@ def choose_protocol(fr: Framing, link: Link, k: int, m_expected: float) -> int:
     return PROTO_FH if t_comm_fh(fr, link, k) <= sh else PROTO_SH
 
 
+RTT_THRESHOLD_S = 10e-3   # Sec. VII "Hardware Implementation": the testbed's switch-over point
+
+
+def select_protocol_by_rtt(rtt_s: float, threshold_s: float = RTT_THRESHOLD_S) -> int:
+    """The testbed's per-request rule (Sec. VII "Hardware Implementation"): the device measures the round-trip time
+    with a light handshake before each request; full-hidden upload when it exceeds the threshold (an extra exchange
+    would cost more than the larger payload), selective-hidden upload otherwise."""
+    if not (rtt_s >= 0.0):
+        raise ValueError("round-trip time must be a non-negative number of seconds")
+    return PROTO_FH if rtt_s > threshold_s else PROTO_SH
+
+
 def end_to_end(rounds) -> float:
     """T_E2E: the sum of the per-round latencies."""
     return float(sum(rounds))
