@@ -40,6 +40,14 @@ TOL_BF16 = Tolerance(p_abs=1e-4, logit_rel=1e-3, hidden_rel=1e-3, tie_margin_rel
 # probabilities <= 5.0e-4; with all five classes 4.6e-3 and 5.4e-4.  The probability bound is the stated one.
 TOL_BF16_MANY = Tolerance(p_abs=1e-3, logit_rel=1e-2, hidden_rel=1e-2, tie_margin_rel=2e-2, tie_margin_abs=0.0, tau_margin=1e-3)
 
+# A cache filled by a real prefill through all 32 layers (instead of synthetic contents written identically on both
+# sides): cached k, v are bf16, so wherever the two sides' float values straddle a rounding boundary an entry differs
+# by a whole bf16 step (2^-9 relative), and those steps feed the later layers and tokens.  Measured at the 8B shape
+# after 64 prefilled tokens: half the entries of the last layer's cache differ by such a step, logits and h^T of the
+# following round agree to 1.7e-3 (5e-5 on identical caches).  Inherent in the bf16-cache contract, well inside the
+# stated 2e-2 / 1e-3.
+TOL_BF16_PREFILL = Tolerance(p_abs=5e-4, logit_rel=5e-3, hidden_rel=5e-3, tie_margin_rel=2e-2, tie_margin_abs=0.0, tau_margin=5e-4)
+
 
 STATS_LOG = []     # (test tag, statistics) of every parity comparison; conftest prints them at the end of the run
 

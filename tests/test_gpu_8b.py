@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity import OracleSide, record, TOL_BF16, TOL_BF16_MANY, check_invariants, check_ss_stream as check_stream, compare_stream, row_rel_err, to_host_weights
+from parity import OracleSide, record, TOL_BF16, TOL_BF16_MANY, TOL_BF16_PREFILL, check_invariants, check_ss_stream as check_stream, compare_stream, row_rel_err, to_host_weights
 from paper_2604_17701_amd import binding
 from wisv_inputs import configs, gen
 from wisv_inputs.configs import PROTO_FH, PROTO_SH
@@ -124,7 +124,7 @@ def test_config2_batch1_ctx4096_k8_selective_hidden(target8b):
 
 
 def test_config3_batch16_ctx2048_k6_tau_sweep(target8b):
-    _run(configs.get(3), target8b, sampled=[0, 11])
+    _run(configs.get(3), target8b, sampled=[0, 5, 11, 15])
 
 
 def test_config3_with_two_bf16_terms_everywhere(target8b):
@@ -134,7 +134,56 @@ def test_config3_with_two_bf16_terms_everywhere(target8b):
 
 
 def test_config4_batch64_ctx8192_k8_mixed_protocols(target8b):
-    _run(configs.get(4), target8b, sampled=[5, 38])     # one SH (odd) and one FH (even) stream
+    _run(configs.get(4), target8b, sampled=[0, 5, 38, 63])     # two FH (even) and two SH (odd) streams, first and last included
+
+
+def test_8b_shape_real_prefill_then_round(target8b):
+    """The cache of the headline shape filled by the library's own prefill (the round's kernels in K-row chunks)
+    instead of synthetic contents: the oracle prefills the same 64 tokens itself, and the two sides are compared
+    cache to cache (three layers, every head and position), by the greedy token after the context, and then on
+    a K = 4 round against those caches.  Cached k, v are bf16 values: an entry differs by a bf16 step wherever the two
+    float results straddle a rounding boundary, and deep layers inherit the steps of the layers before them, so the
+    cache bound is one bf16 step of the largest entry of the plane and the round is held to TOL_BF16_PREFILL."""
+    wd, wh = target8b
+    w = replace(configs.get(1), name="cfg1_shape_real_prefill_l64", ctx=64, kv_source="prefill")
+    m = w.model
+    t0 = time.time()
+    ctx = binding.Context(m, wd, 1, w.ctx + w.k, w.k)
+    toks = gen.context_tokens(w, 0)
+    ctx.wisv_prefill(0, toks)
+    side = OracleSide(w, wh)
+    c = side.orc.new_cache(w.ctx + w.k)
+    side.pred_next[0] = side.orc.prefill(c, toks, chunk=32)
+    side.cache[0] = c
+    print(f"\n[{w.name}] both prefills done at {time.time() - t0:.1f}s", flush=True)
+    stats = {}
+    assert ctx.wisv_get_state(0) == (w.ctx, side.pred_next[0])
+    for layer in (0, m.n_layers // 2, m.n_layers - 1):
+        kg, vg = ctx.wisv_kv_export(0, layer, w.ctx)
+        for name, got, want in (("k", kg, c[layer, 0, :, :w.ctx]), ("v", vg, c[layer, 1, :, :w.ctx])):
+            err = float(np.max(np.abs(got.float().numpy() - want)) / np.max(np.abs(want)))
+            stats[f"kv_rel_l{layer}"] = max(stats.get(f"kv_rel_l{layer}", 0.0), err)
+            assert err <= 2.0 ** -7, (layer, name, err)        # at most one bf16 step of the largest entry
+            frac_equal = float(np.mean(got.float().numpy() == want))
+            stats[f"{name}_equal_l{layer}"] = frac_equal
+            d = np.abs(got.float().numpy() - want)
+            ulp = np.maximum(np.abs(want), 1e-30) * 2.0 ** -7      # at least one bf16 step of the entry itself
+            stats[f"{name}_within_1step_l{layer}"] = float(np.mean(d <= ulp))
+    assert stats["k_equal_l0"] > 0.99 and stats["v_equal_l0"] > 0.99      # the first layer sees identical inputs
+    ins = side.stream_inputs(0)
+    hd, csi = ins.hd, gen.csi_features(w)
+    g = ctx.wisv_verify_round([0], ins.draft, [PROTO_FH], hd, None, csi, [0.5], w.k,
+                              binding.WISV_FLAG_NO_COMMIT | binding.WISV_FLAG_KEEP_LOGITS)
+    check_invariants(g, ins.draft, w.k)
+    logits, hidden = ctx.wisv_debug_copy(binding.WISV_DBG_LOGITS, w.k), ctx.wisv_debug_copy(binding.WISV_DBG_HIDDEN, w.k)
+    o = side.round(0, ins, PROTO_FH, hd, np.arange(w.k), csi[0], 0.5, want_logits=True)
+    stats["logit_rel"], stats["hidden_rel"] = row_rel_err(logits, o["logits"]), row_rel_err(hidden, o["h_t"])
+    tol = TOL_BF16_PREFILL
+    assert stats["logit_rel"] <= tol.logit_rel and stats["hidden_rel"] <= tol.hidden_rel, stats
+    compare_stream(g, 0, o, w.k, 0.5, tol, stats, logits)
+    record(w.name, stats)
+    ctx.wisv_destroy()
+    torch.cuda.empty_cache()
 
 
 def test_config1_shape_speculative_sampling_round(target8b):
