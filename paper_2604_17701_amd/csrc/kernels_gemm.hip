@@ -80,7 +80,7 @@ int ws_padded_row_blocks(int n_rows) { return ((n_rows + 15) / 16 + 15) / 16 * 1
 int ws_padded_pair_blocks(int features) { return ((features + 7) / 8 + 15) / 16 * 16; }
 
 // ------------------------------------------------------------------------------------------ the GEMM
-enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_RESID = 3 };
 
 struct GemmArgs {
     const u32x4 *Wt;           // re-tiled weights [nrb][nkt][64]
@@ -108,6 +108,14 @@ struct GemmArgs {
     const bf16_t *gain;
     int n_partial;
     size_t ys_stride;
+    // EPI_RESID (a product whose k-split stays inside the workgroup: complete sums): v = xin + Y is written to xout,
+    // v * gain to H (float and two-term planes: the next block's RMSNorm without its 1 / rms), and the sum of v^2 over
+    // the workgroup's 16 RB features of every row to ss_out[row-block group][row]; xin may be xout.
+    // EPI_SWIGLU with ss_in: the activations came that way; both halves are scaled by
+    // 1 / sqrt(sum of the n_ss_in partial sums of the row / kd + rms_eps) before the SiLU.
+    const float *ss_in;
+    int n_ss_in;
+    float rms_eps;
 };
 enum { PRO_NONE = 0, PRO_ATTN = 1, PRO_NORM = 2 };
 
@@ -116,7 +124,8 @@ enum { PRO_NONE = 0, PRO_ATTN = 1, PRO_NORM = 2 };
 // partial-output slice, `slot` the wave's candidate slot (one per group of RB row-blocks)
 template <int NT, int RB, int EPI>
 __device__ __forceinline__ void ws_epilogue(const GemmArgs &g, floatx4 (&acc)[RB][NT], int m_base, int rb0, int split,
-                                            int slot, int lane) {
+                                            int slot, int lane, const float *s_inv, const floatx4 (&res_x)[RB][NT],
+                                            const uint2 (&res_g)[RB]) {
     const int bj = lane & 15, bg = lane >> 4;
     if (EPI == EPI_PARTIAL) {
         float *out = g.Yp + (size_t)split * g.split_stride;
@@ -139,6 +148,13 @@ __device__ __forceinline__ void ws_epilogue(const GemmArgs &g, floatx4 (&acc)[RB
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int m = m_base + t * 16 + bj;
+            if (g.ss_in) {   // the deferred 1 / rms of a folded RMSNorm, computed by the kernel's prologue
+                const float inv = s_inv[min(t * 16 + bj, 16 * NT - 1)];
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[r][t][e] *= inv;
+            }
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 floatx4 up;
@@ -158,6 +174,29 @@ __device__ __forceinline__ void ws_epilogue(const GemmArgs &g, floatx4 (&acc)[RB
                             if (f + e < g.N) act_store(g.H, (size_t)m * g.N + f + e, hv[e]);
                 }
             }
+        }
+    } else if (EPI == EPI_RESID) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int m = m_base + t * 16 + bj;
+            float q2 = 0.f;
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const int n = (rb0 + r) * 16 + bg * 4;     // N is a multiple of 16 here (checked by the launcher)
+                if ((rb0 + r) * 16 >= g.N) continue;       // a padding row-block (uniform over the wave)
+                const floatx4 xv = res_x[r][t];            // requested when the kernel started
+                const uint2 gw = res_g[r];
+                const floatx4 v = {xv[0] + acc[r][t][0], xv[1] + acc[r][t][1], xv[2] + acc[r][t][2], xv[3] + acc[r][t][3]};
+                if (m < g.M) {
+                    *reinterpret_cast<floatx4 *>(g.xout + (size_t)m * g.N + n) = v;
+                    act_store4(g.H, (size_t)m * g.N + n, v[0] * __uint_as_float(gw.x << 16), v[1] * __uint_as_float(gw.x & 0xffff0000u),
+                               v[2] * __uint_as_float(gw.y << 16), v[3] * __uint_as_float(gw.y & 0xffff0000u));
+                }
+                q2 += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+            }
+            q2 += __shfl_xor(q2, 16, 64);
+            q2 += __shfl_xor(q2, 32, 64);
+            if (bg == 0 && m < g.M && rb0 * 16 < g.N) g.ss_out[(size_t)slot * g.M + m] = q2;
         }
     } else {   // EPI_ARGMAX: best (value, lowest index) of this wave's 16*RB features for every row
 #pragma unroll
@@ -226,6 +265,21 @@ __global__ __launch_bounds__(64 * WR * WK, PRO == PRO_NORM ? 6 : 1) void k_gemm_
     for (int r = 0; r < RB; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // EPI_RESID: the residual stream and the gain of this wave's outputs are requested now, by the waves that will
+    // run the epilogue (lane (bj, bg): row m_base + 16 t + bj, features 16 (rb0 + r) + 4 bg ..)
+    floatx4 res_x[RB][NT];
+    uint2 res_g[RB];
+    if (EPI == EPI_RESID && wk == 0) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const int n = min((rb0 + r) * 16, g.N - 16) + (lane >> 4) * 4;
+            res_g[r] = *reinterpret_cast<const uint2 *>(g.gain + n);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                res_x[r][t] = *reinterpret_cast<const floatx4 *>(g.xin + (size_t)min(m_base + t * 16 + (lane & 15), g.M - 1) * g.N + n);
+        }
+    }
 
     // ---- activations: chunk ch holds, for every k-slice w, its tiles [ch kcw, (ch+1) kcw) as
     //      lds[ch & 1][plane][w][m][kcw * 64 + 16 bytes]; the 16 spreads rows over the banks
@@ -353,7 +407,31 @@ __global__ __launch_bounds__(64 * WR * WK, PRO == PRO_NORM ? 6 : 1) void k_gemm_
             }
         }
     };
+    // EPI_SWIGLU after a folded RMSNorm: 1 / rms of every row from the partial sums of squares the producer left.
+    // Wave w takes rows w, w + waves, ..; its loads go out before the staging loads and are reduced after them
+    // (lane-strided sums in index order, then a fixed shuffle tree).
+    __shared__ float s_inv[16 * NT];
+    float ssv[4] = {0.f, 0.f, 0.f, 0.f};
+    const bool scale_rows = EPI == EPI_SWIGLU && g.ss_in != nullptr;
+    if (scale_rows && wave < Mt) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ssv[q] = g.ss_in[(size_t)min(lane + 64 * q, g.n_ss_in - 1) * g.M + m_base + wave];
+    }
     stage(0);
+    if (scale_rows) {
+        for (int r = wave; r < Mt; r += NTH / 64) {
+            float v = 0.f;
+            if (r == wave) {   // the first row's partial sums are already here
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v += lane + 64 * q < g.n_ss_in ? ssv[q] : 0.f;
+                for (int p = lane + 256; p < g.n_ss_in; p += 64) v += g.ss_in[(size_t)p * g.M + m_base + r];
+            } else {
+                for (int p = lane; p < g.n_ss_in; p += 64) v += g.ss_in[(size_t)p * g.M + m_base + r];
+            }
+            v = wave_sum(v);
+            if (lane == 0) s_inv[r] = 1.0f / sqrtf(v / (float)g.kd + g.rms_eps);
+        }
+    }
     for (int ch = 0; ch < nchunk; ++ch) {
         __syncthreads();   // chunk ch is staged; everyone is done with the buffer chunk ch + 1 goes to
         if (PRO == PRO_NORM && blockIdx.x == 0 && wave == 0) {
@@ -423,7 +501,7 @@ __global__ __launch_bounds__(64 * WR * WK, PRO == PRO_NORM ? 6 : 1) void k_gemm_
         return;
     }
 
-    ws_epilogue<NT, RB, EPI>(g, acc, m_base, rb0, blockIdx.y, blockIdx.x * WR + wr, lane);
+    ws_epilogue<NT, RB, EPI>(g, acc, m_base, rb0, blockIdx.y, blockIdx.x * WR + wr, lane, s_inv, res_x, res_g);
 }
 
 // ------------------------------------------------------------------------------------------ many rows
@@ -915,16 +993,41 @@ int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_
     return launch_ws_t<1, 1, 8, 1, 4, EPI_PARTIAL, PRO_NORM>(c, g, splits, 40 * 1024) ? splits : 0;
 }
 
+// A product that closes a residual branch, complete inside one kernel (at most 16 rows): one row-block per
+// workgroup, 16 waves split k among them and add their results through LDS, and the epilogue adds the residual
+// stream, writes it back, writes x * gain as the next block's activations and the rows' partial sums of squares to
+// ss[row-block][row] (see EPI_RESID).  `ap`: the activations are still the attention kernel's k-split partials.
+// Returns the number of partial sums per row, 0 if the shape is not served (nothing was launched).
+int launch_gemm_ws_resid(Ctx *c, const void *Wt, const ActBuf &X, const AttnPartials *ap, float *x, const void *gain,
+                         const ActBuf &A_out, float *ss, int rows, int n, int kd, int kclass) {
+    if (rows > 16 || n % 16 || (ap && (ap->splits < 1 || ap->splits > WS_PRO_SPLITS || kd != ap->heads * 128))) return 0;
+    ProfScope ps(c, kclass);
+    GemmArgs g{};
+    fill_args(g, Wt, X, rows, n, kd);
+    g.kt_per_split = g.nkt;
+    g.xin = x; g.xout = x; g.gain = (const bf16_t *)gain; g.H = A_out; g.ss_out = ss;
+    if (ap) {
+        g.att_o = ap->o; g.att_m = ap->m; g.att_l = ap->l;
+        g.att_splits = ap->splits; g.att_rows = ap->rows; g.att_H = ap->heads;
+        return launch_ws_t<1, 1, 1, 16, 4, EPI_RESID, PRO_ATTN>(c, g, 1, 150 * 1024) ? n / 16 : 0;
+    }
+    return launch_ws_t<1, 1, 1, 16, 4, EPI_RESID>(c, g, 1, 150 * 1024) ? n / 16 : 0;
+}
+
 // gate/up with the SwiGLU fused (single split): H[rows][F] = silu(gate) * up.  Every row-block of the
 // re-tiled matrix holds 8 gate and 8 up rows.
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
-                           int kclass, const void *Wh) {
+                           int kclass, const void *Wh, const float *ss, int n_ss) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
     fill_args(g, Wt, X, rows, features, kd);
     g.nrb = ws_padded_pair_blocks(features);
     g.kt_per_split = g.nkt;
     g.H = H;
+    if (n_ss > 0) {   // X holds x * gain: the kernel scales by 1 / rms itself (the streaming kernel only)
+        if (rows > 16) return false;
+        g.ss_in = ss; g.n_ss_in = n_ss; g.rms_eps = c->cfg.rms_eps;
+    }
     if (rows <= 16) {
         // no k-split here, so the workgroup count is fixed by the shape: seven waves per workgroup when that fills
         // whole rounds of 256 CUs better than eight (14336 features: 256 workgroups instead of 224)

@@ -362,6 +362,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     CREATE_TRY(dalloc(c, &c->x, (size_t)R * d));
     CREATE_TRY(dalloc(c, &c->x_alt, (size_t)R * d));
     CREATE_TRY(dalloc(c, &c->ss, (size_t)MAX_SPLITS * R));
+    CREATE_TRY(dalloc(c, &c->ss2, (size_t)((d + 15) / 16) * std::min(R, 16)));
     CREATE_TRY(dalloc(c, &c->y, (size_t)MAX_SPLITS * R * d));
     CREATE_TRY(dalloc(c, &c->qkv, (size_t)MAX_SPLITS * R * c->d_qkv));
     {
@@ -440,8 +441,13 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             }
             return ns;
         };
-        auto gate_up = [&](const LayerW &L) {
-            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, F, d, KC_GEMM_GATEUP, half(L.wgu_h, TERM_GATE_UP))) {
+        auto gate_up = [&](const LayerW &L, int n_ss) {
+            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, F, d, KC_GEMM_GATEUP, half(L.wgu_h, TERM_GATE_UP), c->ss2, n_ss)) {
+                if (n_ss > 0) {   // only the streaming kernel applies the deferred 1 / rms
+                    c->launch_failed = true;
+                    c->launch_err = "gate/up: the streaming kernel does not serve this shape after a folded RMSNorm";
+                    return;
+                }
                 launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
                 launch_swiglu(c, f.rows);
             }
@@ -472,16 +478,29 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
                 if (!launch_attn_mfma(c, f, l, 0)) launch_attn_ref(c, f, l);
             }
             ny = 0;
-            if (defer && att_splits > 1) {
-                if (att_splits <= WS_PRO_SPLITS) {
-                    const AttnPartials ap{c->att_o, c->att_m, c->att_l, att_splits, f.rows, g.n_heads};
-                    ny = launch_gemm_ws_partial(c, L.wo_t, c->o, c->y, ys, MAX_SPLITS, f.rows, d, c->d_q, KC_GEMM, &ap);
-                }
-                if (!ny) launch_attn_combine(c, f, att_splits);   // more splits than the projection takes: a kernel of its own
+            // At most 16 rows: the O projection keeps its k-split inside the workgroup, adds the residual stream itself
+            // and hands x * gain and the rows' sums of squares to gate/up, which applies 1 / rms: the FFN norm's launch
+            // goes too.  It takes the attention's k-split partials as they are when there are few of them.
+            int n_ss2 = 0;
+            if (f.rows <= 16) {
+                const AttnPartials ap{c->att_o, c->att_m, c->att_l, att_splits, f.rows, g.n_heads};
+                const bool partials = defer && att_splits > 1;
+                if (!partials || att_splits <= WS_PRO_SPLITS)
+                    n_ss2 = launch_gemm_ws_resid(c, L.wo_t, c->o, partials ? &ap : nullptr, c->x, L.ffn_norm, c->a, c->ss2, f.rows, d,
+                                                 c->d_q, KC_GEMM);
             }
-            if (!ny) ny = product(L.wo_t, L.wo, half(L.wo_h, TERM_O), c->o, c->y, ys, d, c->d_q);
-            launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
-            gate_up(L);
+            if (!n_ss2) {
+                if (defer && att_splits > 1) {
+                    if (att_splits <= WS_PRO_SPLITS) {
+                        const AttnPartials ap{c->att_o, c->att_m, c->att_l, att_splits, f.rows, g.n_heads};
+                        ny = launch_gemm_ws_partial(c, L.wo_t, c->o, c->y, ys, MAX_SPLITS, f.rows, d, c->d_q, KC_GEMM, &ap);
+                    }
+                    if (!ny) launch_attn_combine(c, f, att_splits);   // more splits than the projection takes: a kernel of its own
+                }
+                if (!ny) ny = product(L.wo_t, L.wo, half(L.wo_h, TERM_O), c->o, c->y, ys, d, c->d_q);
+                launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
+            }
+            gate_up(L, n_ss2);
             ny = product(L.wdown_t, L.wdown, half(L.wdown_h, TERM_DOWN), c->h, c->y, ys, d, F);
         }
         launch_rmsnorm(c, f.rows, ny, c->final_norm, c->a, c->h_t);

@@ -147,6 +147,7 @@ struct Ctx {
     float *x, *y, *qkv, *gu, *h_t, *logits;   // y and qkv hold up to MAX_SPLITS partial slices
     float *x_alt;                 // second residual-stream buffer: a product that folds the norm in reads x and writes here
     float *ss;                    // [MAX_SPLITS][rows_max] sums of squares left by such a product
+    float *ss2;                   // [d_model / 16][min(rows_max, 16)]: those of the O projection that folds the FFN norm in
     float *cand_val;
     int32_t *cand_idx;
     float *q;                     // rotated queries [rows][d_q]
@@ -250,8 +251,12 @@ int launch_gemm_ws_partial(Ctx *c, const void *Wt, const ActBuf &X, float *Yp, s
                            int rows, int n, int kd, int kclass, const AttnPartials *ap = nullptr, const void *Wh = nullptr);
 int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_out, int n_partial, const void *gain,
                             float *Yp, size_t split_stride, int max_splits, int rows, int n, int kd, float *ss, int kclass);
+// n_ss > 0: X holds x * gain of a folded RMSNorm and ss the n_ss partial sums of squares per row ([n_ss][rows]); the
+// kernel applies 1 / rms before the SiLU (at most 16 rows)
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
-                           int kclass, const void *Wh = nullptr);
+                           int kclass, const void *Wh = nullptr, const float *ss = nullptr, int n_ss = 0);
+int launch_gemm_ws_resid(Ctx *c, const void *Wt, const ActBuf &X, const AttnPartials *ap, float *x, const void *gain,
+                         const ActBuf &A_out, float *ss, int rows, int n, int kd, int kclass);
 bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass,
                            const void *Wh = nullptr);
 
