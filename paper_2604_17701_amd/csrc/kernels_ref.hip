@@ -298,7 +298,7 @@ void launch_attn_ref(Ctx *c, const Fwd &f, int layer) {
     const size_t lds = sizeof(float) * (g.head_dim + 260 + f.max_len_ub);
     static bool allowed_bf16[MAX_DEVICES], allowed_f32[MAX_DEVICES];
     const void *kern = c->bf16 ? reinterpret_cast<const void *>(&k_attn_ref<bf16_t, float>) : reinterpret_cast<const void *>(&k_attn_ref<float, float>);
-    if (lds > 160 * 1024 || (lds > 64 * 1024 && !allow_big_lds(c, kern, c->bf16 ? allowed_bf16 : allowed_f32))) {
+    if (lds > 150 * 1024 || (lds > 64 * 1024 && !allow_big_lds(c, kern, c->bf16 ? allowed_bf16 : allowed_f32))) {
         c->launch_failed = true;
         c->launch_err = "the generic attention kernel holds one score per visible position in LDS: a context of " +
                         std::to_string(f.max_len_ub) + " positions does not fit (this shape is not served by the MFMA attention kernel)";

@@ -363,6 +363,7 @@ extern "C" int wisv_ctx_create(const wisv_config *config, const wisv_weights *we
     CREATE_TRY(dalloc(c, &c->x_alt, (size_t)R * d));
     CREATE_TRY(dalloc(c, &c->ss, (size_t)MAX_SPLITS * R));
     CREATE_TRY(dalloc(c, &c->ss2, (size_t)((d + 15) / 16) * std::min(R, 16)));
+    c->graph_refused = false;
     CREATE_TRY(dalloc(c, &c->y, (size_t)MAX_SPLITS * R * d));
     CREATE_TRY(dalloc(c, &c->qkv, (size_t)MAX_SPLITS * R * c->d_qkv));
     {
@@ -679,7 +680,7 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
             c->graph_exec = nullptr;
         }
         bool captured = false;
-        if (same_call) {   // the first call of a kind always runs eagerly (one-time kernel attribute set-up)
+        if (same_call && !c->graph_refused) {   // the first call of a kind always runs eagerly (one-time kernel attribute set-up)
             // Capture, instantiate, launch.  Whatever fails, the capture is ended and its graph dropped, and the round
             // is enqueued eagerly instead: a failed capture must not leave the (possibly borrowed) stream capturing.
             if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal) == hipSuccess) {
@@ -698,6 +699,7 @@ extern "C" int wisv_verify_round(wisv_ctx *ctx, const wisv_round_in *in, wisv_ro
                 }
                 if (graph) (void)hipGraphDestroy(graph);
                 (void)hipGetLastError();   // a capture error is not this round's error: the eager path decides
+                if (!captured) c->graph_refused = true;   // e.g. a launch the capture does not take: do not try every round
             }
         }
         if (!captured && !c->launch_failed) HIP_TRY(c, enqueue_round());

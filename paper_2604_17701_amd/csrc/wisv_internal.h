@@ -148,6 +148,7 @@ struct Ctx {
     float *x_alt;                 // second residual-stream buffer: a product that folds the norm in reads x and writes here
     float *ss;                    // [MAX_SPLITS][rows_max] sums of squares left by such a product
     float *ss2;                   // [d_model / 16][min(rows_max, 16)]: those of the O projection that folds the FFN norm in
+    bool graph_refused;           // a capture of the round failed once: later rounds run eagerly without trying again
     float *cand_val;
     int32_t *cand_idx;
     float *q;                     // rotated queries [rows][d_q]
@@ -281,7 +282,11 @@ inline bool allow_big_lds(const Ctx *c, const void *kernel, bool (&done)[MAX_DEV
     const int dev = c->cfg.device_id;
     if (dev < 0 || dev >= MAX_DEVICES) return false;
     if (done[dev]) return true;
-    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return false;
+    // 150 KiB: what the launchers use at most; the rest of the CU's 160 KiB stays free for a kernel's static LDS
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024) != hipSuccess) {
+        (void)hipGetLastError();   // the caller falls back to another kernel: the refusal is not the round's error
+        return false;
+    }
     done[dev] = true;
     return true;
 }

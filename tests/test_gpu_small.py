@@ -393,6 +393,17 @@ def test_precision_option_is_refused_where_it_cannot_apply():
     ctx.wisv_destroy()
 
 
+@pytest.mark.parametrize("batch,k", [(1, 4), (2, 4), (1, 7)])
+def test_small_bf16_decoder_folded_norms(batch, k):
+    """At most 8 rows and few attention splits: both RMSNorms of a layer are folded into the products around them
+    (QKV with the attention prologue; the O projection with gate/up), on a decoder with a power-of-two FFN width."""
+    model = replace(MID128, d_ff=2048)
+    protos = tuple(PROTO_FH if b % 2 == 0 else PROTO_SH for b in range(batch))
+    w = replace(configs.get(1), model=model, batch=batch, ctx=150, k=k, protos=protos, kv_source="prefill",
+                name=f"mid128_ffn2048_b{batch}_k{k}", index=20 + k, match_rate=(0.5, 0.5))
+    _run_workload(w, TOL_BF16, kv="prefill")
+
+
 def test_small_bf16_decoder_synthetic_kv():
     w = replace(configs.get(2), model=replace(MID, head_dim=128, n_heads=4, n_kv_heads=1), batch=2, ctx=1100, k=8,
                 protos=(PROTO_SH, PROTO_FH), name="mid_bf16_synthkv", index=8)
