@@ -276,7 +276,9 @@ def main():
     d, f, nl = m.d_model, m.d_ff, m.n_layers
     alg_bytes = {
         "gemm_gate_up": nl * 2 * f * d * esz,
-        "gemm_qkv_o_down": nl * (d * (m.d_q + 2 * m.d_kv) + m.d_q * d + d * f) * esz,
+        "gemm_qkv": nl * d * (m.d_q + 2 * m.d_kv) * esz,
+        "gemm_o": nl * m.d_q * d * esz,
+        "gemm_down": nl * d * f * esz,
         "lm_head": m.vocab * d * esz,
         "attention": w.batch * w.ctx * m.kv_bytes_per_token(),
     }
@@ -305,7 +307,7 @@ def main():
     roofline = hbm_roofline(dom)
     # matrix-core work of the three GEMM classes: the method's own FLOP (2 x rows x weights; what the kernels execute
     # for it - two bf16 terms or one half-precision term per activation - is not counted) against the dense bf16 / fp16 peak
-    gemm_classes = [n for n in ("gemm_gate_up", "gemm_qkv_o_down", "lm_head") if n in kernels]
+    gemm_classes = [n for n in ("gemm_gate_up", "gemm_qkv", "gemm_o", "gemm_down", "lm_head") if n in kernels]
     gemm_ms = sum(kernels[n]["ms_per_round"] for n in gemm_classes)
     gemm_flop = 2.0 * w.m * sum(alg_bytes[n] for n in gemm_classes) / esz
     roofline_gemm = None

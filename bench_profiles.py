@@ -151,11 +151,13 @@ def read_hash(path: str):
 
 # position of the epilogue in the template arguments of the two GEMM kernels, and which class an epilogue means
 _EPI_ARG = {"k_gemm_ws": 6, "k_gemm_mm": 7}
-_EPI_CLASS = {"0": "gemm_qkv_o_down", "1": "gemm_gate_up", "2": "lm_head"}
+_EPI_CLASS = {"0": "gemm_qkv_o_down", "1": "gemm_gate_up", "2": "lm_head", "3": "gemm_qkv_o_down"}
 
 
 def kernel_class(kernel: str):
-    """bench.py's kernel class of a (shortened) kernel name, or None."""
+    """bench.py's kernel class of a (shortened) kernel name, or None.  The three k-split products of a layer (QKV, O,
+    down) share kernel templates: a trace cannot tell them apart, so they map to one class that bench.py's per-launch
+    event timing splits further."""
     base, args = template_args(kernel)
     if base == "k_attn_mfma":
         return "attention"

@@ -434,10 +434,10 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         // a product whose shape the streaming kernel cannot serve falls back to the generic kernel (one slice)
         // wh: the half-precision tiles when this product class runs with one term (more than 16 rows only)
         auto half = [&](const void *wh, uint32_t cls) { return f.rows > 16 && (c->one_term_mask & cls) ? wh : nullptr; };
-        auto product = [&](const void *wt, const void *w, const void *wh, const ActBuf &X, float *Yp, size_t stride, int n, int kd) {
-            int ns = launch_gemm_ws_partial(c, wt, X, Yp, stride, MAX_SPLITS, f.rows, n, kd, KC_GEMM, nullptr, wh);
+        auto product = [&](const void *wt, const void *w, const void *wh, const ActBuf &X, float *Yp, size_t stride, int n, int kd, int kclass) {
+            int ns = launch_gemm_ws_partial(c, wt, X, Yp, stride, MAX_SPLITS, f.rows, n, kd, kclass, nullptr, wh);
             if (!ns) {
-                launch_gemm_ref(c, X.f, w, Yp, f.rows, n, kd, KC_GEMM);
+                launch_gemm_ref(c, X.f, w, Yp, f.rows, n, kd, kclass);
                 ns = 1;
             }
             return ns;
@@ -463,12 +463,12 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
             int nq = 0, n_ss = 0;
             if (fuse_rope && f.rows <= 16) {
                 nq = n_ss = launch_gemm_ws_normfold(c, L.wqkv_t, c->x, c->x_alt, ny, L.attn_norm, c->qkv, qs, MAX_SPLITS, f.rows,
-                                                    c->d_qkv, d, c->ss, KC_GEMM);
+                                                    c->d_qkv, d, c->ss, KC_GEMM_QKV);
                 if (nq) std::swap(c->x, c->x_alt);
             }
             if (!nq) {
                 launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
-                nq = product(L.wqkv_t, L.wqkv, half(L.wqkv_h, TERM_QKV), c->a, c->qkv, qs, c->d_qkv, d);
+                nq = product(L.wqkv_t, L.wqkv, half(L.wqkv_h, TERM_QKV), c->a, c->qkv, qs, c->d_qkv, d, KC_GEMM_QKV);
             }
             // with few k-splits and few rows the O projection combines the attention partials while it stages them
             const bool defer = fuse_rope && f.rows <= 16 && g.head_dim == 128;
@@ -488,21 +488,21 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
                 const bool partials = defer && att_splits > 1;
                 if (!partials || att_splits <= WS_PRO_SPLITS)
                     n_ss2 = launch_gemm_ws_resid(c, L.wo_t, c->o, partials ? &ap : nullptr, c->x, L.ffn_norm, c->a, c->ss2, f.rows, d,
-                                                 c->d_q, KC_GEMM);
+                                                 c->d_q, KC_GEMM_O);
             }
             if (!n_ss2) {
                 if (defer && att_splits > 1) {
                     if (att_splits <= WS_PRO_SPLITS) {
                         const AttnPartials ap{c->att_o, c->att_m, c->att_l, att_splits, f.rows, g.n_heads};
-                        ny = launch_gemm_ws_partial(c, L.wo_t, c->o, c->y, ys, MAX_SPLITS, f.rows, d, c->d_q, KC_GEMM, &ap);
+                        ny = launch_gemm_ws_partial(c, L.wo_t, c->o, c->y, ys, MAX_SPLITS, f.rows, d, c->d_q, KC_GEMM_O, &ap);
                     }
                     if (!ny) launch_attn_combine(c, f, att_splits);   // more splits than the projection takes: a kernel of its own
                 }
-                if (!ny) ny = product(L.wo_t, L.wo, half(L.wo_h, TERM_O), c->o, c->y, ys, d, c->d_q);
+                if (!ny) ny = product(L.wo_t, L.wo, half(L.wo_h, TERM_O), c->o, c->y, ys, d, c->d_q, KC_GEMM_O);
                 launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
             }
             gate_up(L, n_ss2);
-            ny = product(L.wdown_t, L.wdown, half(L.wdown_h, TERM_DOWN), c->h, c->y, ys, d, F);
+            ny = product(L.wdown_t, L.wdown, half(L.wdown_h, TERM_DOWN), c->h, c->y, ys, d, F, KC_GEMM_DOWN);
         }
         launch_rmsnorm(c, f.rows, ny, c->final_norm, c->a, c->h_t);
         if (!launch_gemm_ws_argmax(c, c->lm_head_t, c->a, f.keep_logits ? c->logits : nullptr, f.rows, g.vocab, d,
@@ -515,14 +515,14 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
     for (int l = 0; l < g.n_layers; ++l) {
         const LayerW &L = c->layers[l];
         launch_rmsnorm(c, f.rows, l == 0 ? 0 : 1, L.attn_norm, c->a, nullptr);     // + previous FFN update
-        launch_gemm_ref(c, c->a.f, L.wqkv, c->qkv, f.rows, c->d_qkv, d, KC_GEMM);
+        launch_gemm_ref(c, c->a.f, L.wqkv, c->qkv, f.rows, c->d_qkv, d, KC_GEMM_QKV);
         launch_rope_append(c, f, l, 1);
         launch_attn_ref(c, f, l);
-        launch_gemm_ref(c, c->o.f, L.wo, c->y, f.rows, d, c->d_q, KC_GEMM);
+        launch_gemm_ref(c, c->o.f, L.wo, c->y, f.rows, d, c->d_q, KC_GEMM_O);
         launch_rmsnorm(c, f.rows, 1, L.ffn_norm, c->a, nullptr);                   // + attention update
         launch_gemm_ref(c, c->a.f, L.wgu, c->gu, f.rows, 2 * F, d, KC_GEMM_GATEUP);
         launch_swiglu(c, f.rows);
-        launch_gemm_ref(c, c->h.f, L.wdown, c->y, f.rows, d, F, KC_GEMM);
+        launch_gemm_ref(c, c->h.f, L.wdown, c->y, f.rows, d, F, KC_GEMM_DOWN);
     }
     launch_rmsnorm(c, f.rows, 1, c->final_norm, c->a, c->h_t);
     launch_gemm_ref(c, c->a.f, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
@@ -1110,8 +1110,9 @@ extern "C" int wisv_calibration_copy(wisv_ctx *ctx, void *dst, const void *src, 
     return WISV_OK;
 }
 
-static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm_qkv_o_down", "gemm_gate_up", "rope_append", "attention", "attention_combine",
-                                            "swiglu", "lm_head", "argmax", "head", "decide", "spec_sampling", "event_pair_overhead"};
+static const char *kClassNames[KC_COUNT] = {"prep_rows", "embed", "rmsnorm", "gemm_qkv", "gemm_gate_up", "rope_append", "attention", "attention_combine",
+                                            "swiglu", "lm_head", "argmax", "head", "decide", "spec_sampling", "event_pair_overhead",
+                                            "gemm_o", "gemm_down"};
 
 extern "C" int wisv_profile_enable(wisv_ctx *ctx, int32_t on) {
     if (!ctx) return WISV_EINVAL;

@@ -83,8 +83,8 @@ __device__ __forceinline__ void act_store4(const ActBuf &a, size_t i, float v0, 
 
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
 enum KernelClass {
-    KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_LMHEAD,
-    KC_ARGMAX, KC_HEAD, KC_DECIDE, KC_SS, KC_EMPTY, KC_COUNT
+    KC_PREP = 0, KC_EMBED, KC_NORM, KC_GEMM_QKV, KC_GEMM_GATEUP, KC_ROPE, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_LMHEAD,
+    KC_ARGMAX, KC_HEAD, KC_DECIDE, KC_SS, KC_EMPTY, KC_GEMM_O, KC_GEMM_DOWN, KC_COUNT
 };
 
 // ---------------------------------------------------------------- the context
