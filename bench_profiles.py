@@ -77,7 +77,7 @@ def traffic(fetch_csv: str, write_csv: str, out: str, command: str):
 
 def counters(csv_path: str, out: str, command: str):
     """Per-kernel averages of whatever counters one --pmc run collected, plus the matrix-core figures they give:
-    executed bf16 MFMA flop per launch (SQ_INSTS_VALU_MFMA_MOPS_BF16 counts units of 512 flop) and the share of
+    executed bf16 / f16 MFMA flop per launch (SQ_INSTS_VALU_MFMA_MOPS_* count units of 512 flop) and the share of
     the chip's SIMD cycles in which the MFMA unit was busy."""
     agg = collections.defaultdict(lambda: collections.defaultdict(list))
     for r in csv.DictReader(open(csv_path)):
@@ -98,6 +98,8 @@ def counters(csv_path: str, out: str, command: str):
                     f.write(f"    {c:34s} {avg[c]:16.1f}\n")
             if "SQ_INSTS_VALU_MFMA_MOPS_BF16" in avg:
                 f.write(f"    {'executed_bf16_mfma_flop':34s} {avg['SQ_INSTS_VALU_MFMA_MOPS_BF16'] * 512:16.4g}\n")
+            if "SQ_INSTS_VALU_MFMA_MOPS_F16" in avg:
+                f.write(f"    {'executed_f16_mfma_flop':34s} {avg['SQ_INSTS_VALU_MFMA_MOPS_F16'] * 512:16.4g}\n")
             if avg.get("GRBM_GUI_ACTIVE") and "SQ_VALU_MFMA_BUSY_CYCLES" in avg:
                 # GRBM_GUI_ACTIVE comes summed over the 8 XCDs, the MFMA busy cycles over the 1024 SIMDs
                 share = avg["SQ_VALU_MFMA_BUSY_CYCLES"] / (avg["GRBM_GUI_ACTIVE"] / 8 * 1024)
