@@ -500,10 +500,10 @@ void launch_attn_combine(Ctx *c, const Fwd &f, int n_splits) {
     ProfScope ps(c, KC_ATTN_COMBINE);
     if (n_splits <= 4)
         hipLaunchKernelGGL(k_attn_combine<4>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
-                           n_splits, f.rows, g.n_heads, c->o);
+                           n_splits, f.rows, g.n_heads, act_planes(c->o, c->o_planes));
     else
         hipLaunchKernelGGL(k_attn_combine<16>, dim3(f.rows, g.n_heads), dim3(HD), 0, c->stream, c->att_o, c->att_m, c->att_l,
-                           n_splits, f.rows, g.n_heads, c->o);
+                           n_splits, f.rows, g.n_heads, act_planes(c->o, c->o_planes));
 }
 
 // n_partial > 0: the k-split slices of the QKV product are in c->qkv and the kernel does RoPE and the append
@@ -521,7 +521,7 @@ bool launch_attn_mfma(Ctx *c, const Fwd &f, int layer, int n_partial, bool with_
     a.H = g.n_heads; a.G = g.n_kv_heads; a.rep = rep; a.K = f.k; a.max_ctx = g.max_ctx; a.ctx_pad = c->ctx_pad; a.rows = f.rows;
     a.row_slot = c->row_slot; a.row_pos = c->row_pos;
     a.po = c->att_o; a.pm = c->att_m; a.pl = c->att_l;
-    a.o = c->o;
+    a.o = act_planes(c->o, c->o_planes);
     a.qkv = c->qkv; a.n_partial = n_partial; a.partial_stride = (size_t)c->rows_max * c->d_qkv;
     a.cs = c->rope_cos; a.sn = c->rope_sin;
     a.ss = c->ss; a.n_ss = n_ss; a.d_model = g.d_model; a.eps = g.rms_eps;

@@ -1017,7 +1017,7 @@ int launch_gemm_ws_resid(Ctx *c, const void *Wt, const ActBuf &X, const AttnPart
 // gate/up with the SwiGLU fused (single split): H[rows][F] = silu(gate) * up.  Every row-block of the
 // re-tiled matrix holds 8 gate and 8 up rows.
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
-                           int kclass, const void *Wh, const float *ss, int n_ss) {
+                           int kclass, const void *Wh, const float *ss, int n_ss, int planes) {
     ProfScope ps(c, kclass);
     GemmArgs g{};
     fill_args(g, Wt, X, rows, features, kd);
@@ -1035,6 +1035,9 @@ bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf
         if (fill(7) > fill(8)) return launch_ws_t<1, 1, 7, 1, 16, EPI_SWIGLU>(c, g, 1, 36 * 1024);
         return launch_ws_t<1, 1, 8, 1, 16, EPI_SWIGLU>(c, g, 1, 36 * 1024);
     }
+    // more than 16 rows: H has one consumer, the down projection, and `planes` names the representation it reads;
+    // the others (at 512 rows 59 of 73 MB) are not written
+    g.H = act_planes(g.H, planes);
     return launch_ws_many<EPI_SWIGLU>(c, g, 1, mm_layout(rows, g.nrb, g.nkt, false, 1), Wh);
 }
 

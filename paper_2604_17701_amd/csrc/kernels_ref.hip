@@ -118,14 +118,17 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restr
         r.y = v.y * inv * Elem<WT>::load(g + i + 1);
         r.z = v.z * inv * Elem<WT>::load(g + i + 2);
         r.w = v.w * inv * Elem<WT>::load(g + i + 3);
-        *reinterpret_cast<float4 *>(out.f + (size_t)m * d + i) = r;
-        bf16_t h[4], l[4];
-        split2(r.x, h[0], l[0]);
-        split2(r.y, h[1], l[1]);
-        split2(r.z, h[2], l[2]);
-        split2(r.w, h[3], l[3]);
-        *reinterpret_cast<uint2 *>(out.hi + (size_t)m * d + i) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
-        *reinterpret_cast<uint2 *>(out.lo + (size_t)m * d + i) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+        // a representation whose pointer is null has no reader this round and is not written
+        if (out.f) *reinterpret_cast<float4 *>(out.f + (size_t)m * d + i) = r;
+        if (out.hi) {
+            bf16_t h[4], l[4];
+            split2(r.x, h[0], l[0]);
+            split2(r.y, h[1], l[1]);
+            split2(r.z, h[2], l[2]);
+            split2(r.w, h[3], l[3]);
+            *reinterpret_cast<uint2 *>(out.hi + (size_t)m * d + i) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+            *reinterpret_cast<uint2 *>(out.lo + (size_t)m * d + i) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+        }
         if (out.h16)
             *reinterpret_cast<uint2 *>(out.h16 + (size_t)m * d + i) = make_uint2(f32_to_f16(r.x) | ((uint32_t)f32_to_f16(r.y) << 16),
                                                                                  f32_to_f16(r.z) | ((uint32_t)f32_to_f16(r.w) << 16));
@@ -309,11 +312,11 @@ void launch_attn_ref(Ctx *c, const Fwd &f, int layer) {
     if (c->bf16)
         hipLaunchKernelGGL((k_attn_ref<bf16_t, float>), grid, dim3(256), lds, c->stream, (const float *)c->q,
                            (const bf16_t *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, c->ctx_pad,
-                           c->row_slot, c->row_pos, c->o);
+                           c->row_slot, c->row_pos, act_planes(c->o, c->o_planes));
     else
         hipLaunchKernelGGL((k_attn_ref<float, float>), grid, dim3(256), lds, c->stream, (const float *)c->q,
                            (const float *)kvl, slot_stride, g.n_heads, g.n_kv_heads, g.head_dim, c->ctx_pad, c->row_slot,
-                           c->row_pos, c->o);
+                           c->row_pos, act_planes(c->o, c->o_planes));
 }
 
 // ------------------------------------------------------------------------------------------ V plane <-> rows

@@ -427,6 +427,7 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
     const int d = g.d_model, F = g.d_ff;
     launch_prep_rows(c, f);
     launch_embed(c, f);
+    c->o_planes = ACT_ALL;
     if (c->ws_ok) {
         // bf16 weight-streaming path: every product leaves k-split partial slices that the next
         // kernel sums in a fixed order; gate/up and the LM head fuse SwiGLU / argmax instead
@@ -434,16 +435,37 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         // a product whose shape the streaming kernel cannot serve falls back to the generic kernel (one slice)
         // wh: the half-precision tiles when this product class runs with one term (more than 16 rows only)
         auto half = [&](const void *wh, uint32_t cls) { return f.rows > 16 && (c->one_term_mask & cls) ? wh : nullptr; };
-        auto product = [&](const void *wt, const void *w, const void *wh, const ActBuf &X, float *Yp, size_t stride, int n, int kd, int kclass) {
+        // have_f: the float plane of X is current (the generic kernel reads that one)
+        auto product = [&](const void *wt, const void *w, const void *wh, const ActBuf &X, float *Yp, size_t stride, int n, int kd, int kclass,
+                           bool have_f = true) {
             int ns = launch_gemm_ws_partial(c, wt, X, Yp, stride, MAX_SPLITS, f.rows, n, kd, kclass, nullptr, wh);
             if (!ns) {
+                if (!have_f) {
+                    c->launch_failed = true;
+                    c->launch_err = "a product fell back to the generic kernel after its input was written without the float plane";
+                    return 1;
+                }
                 launch_gemm_ref(c, X.f, w, Yp, f.rows, n, kd, kclass);
                 ns = 1;
             }
             return ns;
         };
+        // Beyond 16 rows an activation buffer is written in the one representation its consumer reads: the half
+        // plane when that product class runs with one term, else the two bf16 planes; never the float plane
+        auto planes_for = [&](const void *wh) { return f.rows <= 16 ? ACT_ALL : wh && c->a.h16 ? ACT_HALF : ACT_TWO_TERM; };
+        const bool full = f.rows <= 16;   // every representation is written
+        if (g.n_layers) c->o_planes = planes_for(half(c->layers[0].wo_h, TERM_O));
+        bool h_has_f = true;
         auto gate_up = [&](const LayerW &L, int n_ss) {
-            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, F, d, KC_GEMM_GATEUP, half(L.wgu_h, TERM_GATE_UP), c->ss2, n_ss)) {
+            h_has_f = full;
+            if (!launch_gemm_ws_swiglu(c, L.wgu_t, c->a, c->h, f.rows, F, d, KC_GEMM_GATEUP, half(L.wgu_h, TERM_GATE_UP), c->ss2, n_ss,
+                                       planes_for(half(L.wdown_h, TERM_DOWN)))) {
+                if (!full) {   // c->a came without its float plane
+                    c->launch_failed = true;
+                    c->launch_err = "gate/up fell back to the generic kernel after its input was written without the float plane";
+                    return;
+                }
+                h_has_f = true;
                 if (n_ss > 0) {   // only the streaming kernel applies the deferred 1 / rms
                     c->launch_failed = true;
                     c->launch_err = "gate/up: the streaming kernel does not serve this shape after a folded RMSNorm";
@@ -467,8 +489,8 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
                 if (nq) std::swap(c->x, c->x_alt);
             }
             if (!nq) {
-                launch_rmsnorm(c, f.rows, ny, L.attn_norm, c->a, nullptr);
-                nq = product(L.wqkv_t, L.wqkv, half(L.wqkv_h, TERM_QKV), c->a, c->qkv, qs, c->d_qkv, d, KC_GEMM_QKV);
+                launch_rmsnorm(c, f.rows, ny, L.attn_norm, act_planes(c->a, planes_for(half(L.wqkv_h, TERM_QKV))), nullptr);
+                nq = product(L.wqkv_t, L.wqkv, half(L.wqkv_h, TERM_QKV), c->a, c->qkv, qs, c->d_qkv, d, KC_GEMM_QKV, full);
             }
             // with few k-splits and few rows the O projection combines the attention partials while it stages them
             const bool defer = fuse_rope && f.rows <= 16 && g.head_dim == 128;
@@ -498,15 +520,20 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
                     }
                     if (!ny) launch_attn_combine(c, f, att_splits);   // more splits than the projection takes: a kernel of its own
                 }
-                if (!ny) ny = product(L.wo_t, L.wo, half(L.wo_h, TERM_O), c->o, c->y, ys, d, c->d_q, KC_GEMM_O);
-                launch_rmsnorm(c, f.rows, ny, L.ffn_norm, c->a, nullptr);
+                if (!ny) ny = product(L.wo_t, L.wo, half(L.wo_h, TERM_O), c->o, c->y, ys, d, c->d_q, KC_GEMM_O, full);
+                launch_rmsnorm(c, f.rows, ny, L.ffn_norm, act_planes(c->a, planes_for(half(L.wgu_h, TERM_GATE_UP))), nullptr);
             }
             gate_up(L, n_ss2);
-            ny = product(L.wdown_t, L.wdown, half(L.wdown_h, TERM_DOWN), c->h, c->y, ys, d, F, KC_GEMM_DOWN);
+            ny = product(L.wdown_t, L.wdown, half(L.wdown_h, TERM_DOWN), c->h, c->y, ys, d, F, KC_GEMM_DOWN, h_has_f);
         }
-        launch_rmsnorm(c, f.rows, ny, c->final_norm, c->a, c->h_t);
+        launch_rmsnorm(c, f.rows, ny, c->final_norm, act_planes(c->a, planes_for(half(c->lm_head_h, TERM_LM_HEAD))), c->h_t);
         if (!launch_gemm_ws_argmax(c, c->lm_head_t, c->a, f.keep_logits ? c->logits : nullptr, f.rows, g.vocab, d,
                                    KC_LMHEAD, half(c->lm_head_h, TERM_LM_HEAD))) {
+            if (!full) {
+                c->launch_failed = true;
+                c->launch_err = "the LM head fell back to the generic kernel after its input was written without the float plane";
+                return;
+            }
             launch_gemm_ref(c, c->a.f, c->lm_head, c->logits, f.rows, g.vocab, d, KC_LMHEAD);
             launch_argmax(c, f.rows);
         }

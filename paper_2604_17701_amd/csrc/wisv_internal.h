@@ -57,28 +57,44 @@ __device__ __forceinline__ void split2(float v, bf16_t &hi, bf16_t &lo) {
     hi = f32_to_bf16(v);
     lo = f32_to_bf16(v - bf16_to_f32(hi));
 }
+// A plane whose pointer is null is not written (f; hi and lo together; h16): a producer whose only consumer reads
+// one representation leaves the others out.
 __device__ __forceinline__ void act_store(const ActBuf &a, size_t i, float v) {
-    bf16_t h, l;
-    split2(v, h, l);
-    a.f[i] = v;
-    a.hi[i] = h;
-    a.lo[i] = l;
+    if (a.f) a.f[i] = v;
+    if (a.hi) {
+        bf16_t h, l;
+        split2(v, h, l);
+        a.hi[i] = h;
+        a.lo[i] = l;
+    }
     if (a.h16) a.h16[i] = f32_to_f16(v);
 }
 
 // four consecutive elements, i a multiple of 4: one 16-byte and two 8-byte stores
 __device__ __forceinline__ void act_store4(const ActBuf &a, size_t i, float v0, float v1, float v2, float v3) {
-    bf16_t h[4], l[4];
-    split2(v0, h[0], l[0]);
-    split2(v1, h[1], l[1]);
-    split2(v2, h[2], l[2]);
-    split2(v3, h[3], l[3]);
-    *reinterpret_cast<float4 *>(a.f + i) = make_float4(v0, v1, v2, v3);
-    *reinterpret_cast<uint2 *>(a.hi + i) = make_uint2(h[0] | ((unsigned)h[1] << 16), h[2] | ((unsigned)h[3] << 16));
-    *reinterpret_cast<uint2 *>(a.lo + i) = make_uint2(l[0] | ((unsigned)l[1] << 16), l[2] | ((unsigned)l[3] << 16));
+    if (a.f) *reinterpret_cast<float4 *>(a.f + i) = make_float4(v0, v1, v2, v3);
+    if (a.hi) {
+        bf16_t h[4], l[4];
+        split2(v0, h[0], l[0]);
+        split2(v1, h[1], l[1]);
+        split2(v2, h[2], l[2]);
+        split2(v3, h[3], l[3]);
+        *reinterpret_cast<uint2 *>(a.hi + i) = make_uint2(h[0] | ((unsigned)h[1] << 16), h[2] | ((unsigned)h[3] << 16));
+        *reinterpret_cast<uint2 *>(a.lo + i) = make_uint2(l[0] | ((unsigned)l[1] << 16), l[2] | ((unsigned)l[3] << 16));
+    }
     if (a.h16)
         *reinterpret_cast<uint2 *>(a.h16 + i) = make_uint2(f32_to_f16(v0) | ((unsigned)f32_to_f16(v1) << 16),
                                                            f32_to_f16(v2) | ((unsigned)f32_to_f16(v3) << 16));
+}
+
+// Which representations of an activation buffer a producer writes: all of them, or only the one its single consumer
+// reads (beyond 16 rows, where these buffers are tens of megabytes)
+enum { ACT_ALL = 0, ACT_TWO_TERM = 1, ACT_HALF = 2 };
+// the buffer with the pointers of the representations that `planes` leaves out set to null (producers skip those)
+inline ActBuf act_planes(ActBuf a, int planes) {
+    if (planes == ACT_HALF && a.h16) a.f = nullptr, a.hi = a.lo = nullptr;
+    else if (planes == ACT_TWO_TERM) a.f = nullptr, a.h16 = nullptr;
+    return a;
 }
 
 // ---------------------------------------------------------------- kernel classes (for per-kernel timing)
@@ -153,6 +169,7 @@ struct Ctx {
     int32_t *cand_idx;
     float *q;                     // rotated queries [rows][d_q]
     ActBuf a, o, h;               // normalised activations, attention output, SwiGLU output
+    int o_planes;                 // ACT_*: the representations of o that this round's attention kernels write
     float *hu;                    // decision head: second-layer partial sums [row-block of hidden units][row]
     float *att_o, *att_m, *att_l; // split-KV attention partials: [split][rows][heads][head_dim], [split][rows][heads]
     int att_max_splits;
@@ -254,8 +271,9 @@ int launch_gemm_ws_normfold(Ctx *c, const void *Wt, const float *x_in, float *x_
                             float *Yp, size_t split_stride, int max_splits, int rows, int n, int kd, float *ss, int kclass);
 // n_ss > 0: X holds x * gain of a folded RMSNorm and ss the n_ss partial sums of squares per row ([n_ss][rows]); the
 // kernel applies 1 / rms before the SiLU (at most 16 rows)
+// planes: one of ACT_* (more than 16 rows only): the kernel writes no other representation of H
 bool launch_gemm_ws_swiglu(Ctx *c, const void *Wt, const ActBuf &X, const ActBuf &H, int rows, int features, int kd,
-                           int kclass, const void *Wh = nullptr, const float *ss = nullptr, int n_ss = 0);
+                           int kclass, const void *Wh = nullptr, const float *ss = nullptr, int n_ss = 0, int planes = ACT_ALL);
 int launch_gemm_ws_resid(Ctx *c, const void *Wt, const ActBuf &X, const AttnPartials *ap, float *x, const void *gain,
                          const ActBuf &A_out, float *ss, int rows, int n, int kd, int kclass);
 bool launch_gemm_ws_argmax(Ctx *c, const void *Wt, const ActBuf &X, float *logits, int rows, int n, int kd, int kclass,
