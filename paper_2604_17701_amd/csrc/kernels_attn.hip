@@ -30,7 +30,7 @@ struct AttnArgs {
     size_t slot_stride;       // elements per slot
     int H, G, rep, K, max_ctx, ctx_pad, n_splits, rows;
     const int32_t *row_slot, *row_pos;
-    float *po, *pm, *pl;      // partials [split][rows][H][128], [split][rows][H]  (n_splits > 1)
+    float *po, *pm, *pl;      // partials [split][rows][H][128], [split][rows][H]  (n_splits > 1); pm in units of ln 2
     ActBuf o;                 // attention output [rows][H][128]                    (n_splits == 1)
     // FUSE: the kernel sums the k-split slices of the QKV product itself, rotates q and k, appends k and v
     const float *qkv;         // [n_partial][partial_stride] slices of [rows][H*128 + 2 G*128]
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         for (int dt = 0; dt < 8; ++dt) oacc[nq][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
+    const float scale = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(128): scores in units of ln 2
     for (; s < s_end; s += NW) {
         const int kbase = s * STEP + 8 * bg;     // this lane's eight keys: kbase .. kbase + 7
         const int s_next = min(s + NW, n_steps - 1);
@@ -304,26 +304,40 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
             const int rho = nq * 16 + bj;
             const int qpos = L + rho / a.rep;
             float sv[8], mx = -INFINITY;
+            if (s * STEP + STEP - 1 <= L) {
+                // every query of the block sees every key of this step (wave-uniform): no mask.  Rows past R hold
+                // zero queries; their scores are finite and never stored.
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int kp = kbase + e;
-                const float x = e < 4 ? sa[e] : sb[e - 4];
-                sv[e] = (rho < R && kp <= qpos && kp < n_keys) ? x * scale : -INFINITY;
-                mx = fmaxf(mx, sv[e]);
+                for (int e = 0; e < 8; ++e) {
+                    sv[e] = (e < 4 ? sa[e] : sb[e - 4]) * scale;
+                    mx = fmaxf(mx, sv[e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int kp = kbase + e;
+                    const float x = e < 4 ? sa[e] : sb[e - 4];
+                    sv[e] = (rho < R && kp <= qpos && kp < n_keys) ? x * scale : -INFINITY;
+                    mx = fmaxf(mx, sv[e]);
+                }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            // Scores are in units of ln 2, so the exponentials are single v_exp_f32 instructions; exp2(-inf) = 0 covers
+            // masked keys and a row's first step, and a row that has seen no key at all subtracts 0 instead of -inf.
             const float m_new = fmaxf(m_run[nq], mx);
-            float alpha = 1.f, p[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if (m_new != -INFINITY) {
-                alpha = m_run[nq] == -INFINITY ? 0.f : expf(m_run[nq] - m_new);
+            const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_sub);
+            float p[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) p[e] = sv[e] == -INFINITY ? 0.f : expf(sv[e] - m_new);
-            }
+            for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(sv[e] - m_sub);
             l_run[nq] = l_run[nq] * alpha + (((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7])));
             m_run[nq] = m_new;
+            // the running maximum rarely moves after a row's first steps: scaling by exactly 1 is skipped (wave-uniform)
+            if (__any(alpha != 1.f)) {
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) oacc[nq][dt] *= alpha;
+                for (int dt = 0; dt < 8; ++dt) oacc[nq][dt] *= alpha;
+            }
             uint32_t h[4], l[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -394,11 +408,11 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
         float ls = 0.f;
         for (int w = 0; w < NW; ++w) {
             const float mw = sm[(w * NQ + nq) * 16 + bj];
-            if (mw != -INFINITY) ls += sl[(w * NQ + nq) * 16 + bj] * expf(mw - mx);
+            if (mw != -INFINITY) ls += sl[(w * NQ + nq) * 16 + bj] * exp2f(mw - mx);
         }
         m_all[nq] = mx;
         l_all[nq] = ls;
-        const float mine = m_run[nq] == -INFINITY ? 0.f : expf(m_run[nq] - mx);
+        const float mine = m_run[nq] == -INFINITY ? 0.f : exp2f(m_run[nq] - mx);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) so[((wave * NQ + nq) * 8 + dt) * 64 + lane] = oacc[nq][dt] * mine;
     }
@@ -427,7 +441,8 @@ __global__ __launch_bounds__(64 * NW) void k_attn_mfma(AttnArgs a) {
     }
 }
 
-// o[m][h][:] = sum_s e^(m_s - m*) O_s / sum_s e^(m_s - m*) l_s, splits in index order; one block per (row, head).
+// o[m][h][:] = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s (the maxima are kept in units of ln 2), splits in index
+// order; one block per (row, head).
 // Splits are taken BATCH at a time, all loads of a batch issued before the first is used (slots past the last
 // split re-read it and weigh zero), batches chained with the same rescaling rule.
 template <int BATCH>
@@ -448,13 +463,13 @@ __global__ void k_attn_combine(const float *__restrict__ po, const float *__rest
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) bmx = fmaxf(bmx, s0 + i < n_splits ? ms[i] : -INFINITY);
         if (bmx == -INFINITY) continue;
-        const float keep = mx == -INFINITY ? 0.f : expf(mx - bmx);
+        const float keep = mx == -INFINITY ? 0.f : exp2f(mx - bmx);
         num *= keep;
         den *= keep;
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
             const bool on = s0 + i < n_splits && ms[i] != -INFINITY;
-            const float w = on ? expf(ms[i] - bmx) : 0.f;
+            const float w = on ? exp2f(ms[i] - bmx) : 0.f;
             den = fmaf(w, on ? ls[i] : 0.f, den);
             num = fmaf(w, on ? os[i] : 0.f, num);
         }

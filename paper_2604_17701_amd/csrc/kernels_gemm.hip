@@ -96,7 +96,7 @@ struct GemmArgs {
     int n_cand;
     int gx, gz, gs;            // k_gemm_mm: row-block groups, row tiles and k-splits the 1-D grid decodes into
     // PRO: the activations are the attention output, still in k-split partials (up to WS_PRO_SPLITS of them):
-    // o [split][rows][heads][128], running maximum m and sum l [split][rows][heads]
+    // o [split][rows][heads][128], running maximum m (in units of ln 2) and sum l [split][rows][heads]
     const float *att_o, *att_m, *att_l;
     int att_splits, att_rows, att_H;
     // PRO_NORM: the activations are the residual stream, still to be updated: v = xin + the n_partial slices of the
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(64 * WR * WK, PRO == PRO_NORM ? 6 : 1) void k_gemm_
 #pragma unroll
                     for (int sp = 0; sp < WS_PRO_SPLITS; ++sp) {
                         const bool on = sp < g.att_splits && ms[sp] != -INFINITY;
-                        const float wgt = on ? expf(ms[sp] - mx) : 0.f;
+                        const float wgt = on ? exp2f(ms[sp] - mx) : 0.f;   // the maxima are in units of ln 2
                         den = fmaf(wgt, on ? ls[sp] : 0.f, den);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
