@@ -82,7 +82,8 @@ void launch_embed(Ctx *c, const Fwd &f) {
 
 // ------------------------------------------------------------------------------------------ RMSNorm
 // x[m] += y[0][m] + ... + y[n_partial-1][m] (fixed order), then out[m] = x[m] / sqrt(mean(x^2)+eps) * g
-template <typename WT, typename AT>
+// NP: the most slices a launch may hold (the loads of all NP are issued whatever n_partial is)
+template <typename WT, typename AT, int NP>
 __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restrict__ y, int n_partial, size_t partial_stride,
                           const WT *__restrict__ g, int d, float eps, ActBuf out, float *out_f32) {
     __shared__ float red[16];
@@ -95,13 +96,13 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restr
     float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i = threadIdx.x * 4; i < d; i += 4096) {
         float4 v = *reinterpret_cast<const float4 *>(xr + i);
-        float4 part[MAX_SPLITS];
+        float4 part[NP];
         const int np = max(n_partial, 1);
 #pragma unroll
-        for (int p = 0; p < MAX_SPLITS; ++p)
+        for (int p = 0; p < NP; ++p)
             part[p] = *reinterpret_cast<const float4 *>(y + (size_t)min(p, np - 1) * partial_stride + (size_t)m * d + i);
 #pragma unroll
-        for (int p = 0; p < MAX_SPLITS; ++p) {
+        for (int p = 0; p < NP; ++p) {
             const bool on = p < n_partial;   // a select, not a product: the unused re-read may hold anything
             v.x += on ? part[p].x : 0.f; v.y += on ? part[p].y : 0.f; v.z += on ? part[p].z : 0.f; v.w += on ? part[p].w : 0.f;
         }
@@ -136,16 +137,25 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(float *x, const float *__restr
     }
 }
 
-void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, const ActBuf &out, float *out_f32) {
-    ProfScope ps(c, KC_NORM);
+template <int NP>
+static void launch_rmsnorm_np(Ctx *c, int rows, int n_partial, const void *g, const ActBuf &out, float *out_f32) {
     const int d = c->cfg.d_model;
     const size_t stride = (size_t)c->rows_max * d;
     if (c->bf16)
-        hipLaunchKernelGGL((k_rmsnorm<bf16_t, float>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
+        hipLaunchKernelGGL((k_rmsnorm<bf16_t, float, NP>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
                            stride, (const bf16_t *)g, d, c->cfg.rms_eps, out, out_f32);
     else
-        hipLaunchKernelGGL((k_rmsnorm<float, float>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
+        hipLaunchKernelGGL((k_rmsnorm<float, float, NP>), dim3(rows), dim3(1024), 0, c->stream, c->x, c->y, n_partial,
                            stride, (const float *)g, d, c->cfg.rms_eps, out, out_f32);
+}
+
+void launch_rmsnorm(Ctx *c, int rows, int n_partial, const void *g, const ActBuf &out, float *out_f32) {
+    ProfScope ps(c, KC_NORM);
+    static_assert(MAX_SPLITS <= 16, "the widest instantiation below covers every slice count");
+    // the kernel requests as many slices as its instantiation holds: the smallest one that covers n_partial
+    if (n_partial <= 4) launch_rmsnorm_np<4>(c, rows, n_partial, g, out, out_f32);
+    else if (n_partial <= 8) launch_rmsnorm_np<8>(c, rows, n_partial, g, out, out_f32);
+    else launch_rmsnorm_np<16>(c, rows, n_partial, g, out, out_f32);
 }
 
 // ------------------------------------------------------------------------------------------ GEMM (fallback)
