@@ -607,7 +607,7 @@ template <int NPL> __device__ __forceinline__ floatx16 mm_mfma(const u32x4 &a, c
     if (NPL == 2) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&a), *reinterpret_cast<const bf16x8 *>(&b), c, 0, 0, 0);
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const f16x8 *>(&a), *reinterpret_cast<const f16x8 *>(&b), c, 0, 0, 0);
 }
-template <int NT, int WM, int NW, int WK, int RP, int KC, int U, int EPI, int NPL>
+template <int NT, int WM, int NW, int WK, int RP, int KC, int U, int EPI, int NPL, bool DEEP = false>
 __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char lds[];
     static_assert(KC % WK == 0, "every k-slice takes the same number of k-tiles of a chunk");
@@ -663,18 +663,20 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     static_assert((NPL * OPS) % NW == 0, "every wave stages the same number of operands");
     const int srow = m_base + (lane & 31);
     const int scol = (lane >> 5) * 16;
-    u32x4 sreg[PER_WAVE];
-#define WISV_MM_STAGE_LOAD(ch)                                                                                     \
+    constexpr int TURN = U / KW;   // chunks per turn of the ring
+    constexpr int SD = DEEP ? TURN : 1;   // chunks of activations in flight
+    u32x4 sreg[SD][PER_WAVE];
+#define WISV_MM_STAGE_LOAD(ch, S)                                                                                   \
     _Pragma("unroll") for (int j = 0; j < PER_WAVE; ++j) {                                                         \
         const int i = wave + NW * j, pl = i / OPS, rem = i % OPS, lt = rem / (2 * NTW), t = (rem / 2) % NTW, op = rem & 1; \
         const int kt = min((ch) * KC + lt, ntile - 1);                                                             \
         const int row = min(srow + 32 * t, g.M - 1);                                                               \
-        sreg[j] = *reinterpret_cast<const u32x4 *>((NPL == 1 ? g.X16 : pl ? g.Xlo : g.Xhi) + (size_t)row * g.kd +  \
+        sreg[S][j] = *reinterpret_cast<const u32x4 *>((NPL == 1 ? g.X16 : pl ? g.Xlo : g.Xhi) + (size_t)row * g.kd +  \
                                                    (size_t)(kt0 + kt) * 32 + 8 * op + scol);                       \
     }
-#define WISV_MM_STAGE_STORE(ch)                                                                                    \
+#define WISV_MM_STAGE_STORE(ch, S)                                                                                  \
     _Pragma("unroll") for (int j = 0; j < PER_WAVE; ++j)                                                           \
-        *reinterpret_cast<u32x4 *>(lds + (size_t)((ch) & 1) * BUF + (size_t)(wave + NW * j) * 1024 + lane * 16) = sreg[j];
+        *reinterpret_cast<u32x4 *>(lds + (size_t)((ch) & 1) * BUF + (size_t)(wave + NW * j) * 1024 + lane * 16) = sreg[S][j];
     // A k-tile is G groups (op, plane) of NT B operands, each feeding NT RP independent MFMAs.  The B
     // operands of group gi + 1 are read from LDS before the MFMAs of group gi issue (scheduling barriers keep
     // that order): the LDS latency hides behind matrix work, the other wave of the SIMD fills what is left.
@@ -686,19 +688,22 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
     _Pragma("unroll") for (int t = 0; t < NT; ++t) _Pragma("unroll") for (int p = 0; p < RP; ++p)                  \
         acc[p][t] = mm_mfma<NPL>(A[p][(og) / NPL], SRC[t], acc[p][t]);
     u32x4 bv[2][NT];
-    constexpr int TURN = U / KW;   // chunks per turn of the ring
 
     // One chunk: CC (a compile-time number) places it in a turn of the weight ring, which spans U / KC chunks.
     // The next chunk's activations are requested before this chunk's MFMAs and written to LDS after them; the
     // write must wait for exactly these loads while the weight refills issued after them stay in flight, and
     // the compiler can count those only if every path through the chunk issues the same number of loads.
+    // Loads complete in order, so that wait also ends every weight refill issued before them, which caps the ring
+    // at about one chunk whatever U is.  DEEP keeps as many chunks of activations in flight as the ring has
+    // (requested right after the previous occupant of their registers went to LDS, a whole turn before they are
+    // written): the wait then ends only refills that are due in the same chunk anyway.
 #define WISV_MM_CHUNK(ch, CC)                                                                                      \
     {                                                                                                              \
         __syncthreads(); /* chunk ch is in LDS; nobody still reads the buffer chunk ch + 1 goes to */             \
         /* this wave's row tiles start at tile wm NT of the workgroup's */                                        \
         const unsigned char *buf = lds + (size_t)((ch) & 1) * BUF + (size_t)(wm * NT) * 2048 + lane * 16;          \
         const int kbase = (ch) * KC;                                                                               \
-        WISV_MM_STAGE_LOAD((ch) + 1)                                                                               \
+        if (!DEEP) { WISV_MM_STAGE_LOAD((ch) + 1, 0) }                                                             \
         _Pragma("unroll") for (int lw = 0; lw < KW; ++lw) {                                                        \
             const int lt = wk * KW + lw; /* this wave's k-tile of the chunk */                                    \
             if (kbase + lt < ntile) { /* uniform per wave; no load inside, so the load counts hold on every path */ \
@@ -715,12 +720,20 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_mm(GemmArgs g) {
                 abuf[(CC) * KW + lw][p][op] = wp[p * wstep + (size_t)min(kbase + lt + TURN * KC, ntile - 1) * 64 + 16 * op]; \
             __builtin_amdgcn_sched_barrier(0);                                                                     \
         }                                                                                                          \
-        WISV_MM_STAGE_STORE((ch) + 1)                                                                              \
+        WISV_MM_STAGE_STORE((ch) + 1, DEEP ? ((CC) + 1) % TURN : 0)                                                \
+        if (DEEP) { WISV_MM_STAGE_LOAD((ch) + 1 + TURN, ((CC) + 1) % TURN) }                                       \
     }
 
     const int nchunk = (ntile + KC - 1) / KC;
-    WISV_MM_STAGE_LOAD(0)
-    WISV_MM_STAGE_STORE(0)
+    if (DEEP) {
+#pragma unroll
+        for (int cc = 0; cc < TURN; ++cc) { WISV_MM_STAGE_LOAD(cc, cc) }
+        WISV_MM_STAGE_STORE(0, 0)
+        WISV_MM_STAGE_LOAD(TURN, 0)
+    } else {
+        WISV_MM_STAGE_LOAD(0, 0)
+        WISV_MM_STAGE_STORE(0, 0)
+    }
     int ch = 0;
     for (; ch + TURN <= nchunk; ch += TURN) {   // whole turns: no branch around any load
 #pragma unroll
@@ -846,7 +859,7 @@ static bool launch_ws_t(Ctx *c, GemmArgs &g, int splits, size_t soft_budget) {
 constexpr int MM_RP = 2;            // pairs of row-blocks per wave of k_gemm_mm
 constexpr int MM_RB = 2 * MM_RP;
 
-template <int NT, int WM, int NW, int WK, int KC, int U, int EPI, int NPL>
+template <int NT, int WM, int NW, int WK, int KC, int U, int EPI, int NPL, bool DEEP = false>
 static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
     constexpr int WN = NW / (WM * WK), NTW = NT * WM;
     g.gx = (g.nrb + WN * MM_RB - 1) / (WN * MM_RB);
@@ -856,10 +869,10 @@ static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
     const size_t lds = std::max((size_t)2 * NPL * KC * NTW * 2 * 1024, WK > 1 ? (size_t)WN * WM * MM_RP * NT * 4096 : (size_t)0);
     static bool allowed[MAX_DEVICES];     // per instantiation
     if (lds > 64 * 1024 &&
-        !allow_big_lds(c, reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL>), allowed))
+        !allow_big_lds(c, reinterpret_cast<const void *>(&k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL, DEEP>), allowed))
         return false;
     const unsigned grid = (unsigned)((g.gx * g.gs + 7) / 8 * 8 * g.gz);
-    hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
+    hipLaunchKernelGGL((k_gemm_mm<NT, WM, NW, WK, MM_RP, KC, U, EPI, NPL, DEEP>), dim3(grid), dim3(64 * NW), lds, c->stream, g);
     return true;
 }
 
@@ -913,7 +926,12 @@ template <int EPI, int NPL> static bool launch_ws_many_t(Ctx *c, GemmArgs &g, in
     }
     if (g.M <= 64) return launch_mm_t<2, 1, 8, 1, 2, 2, EPI, NPL>(c, g, splits);
     if (layout == MM_WIDE) return launch_mm_t<4, 1, 8, 1, 2, 2, EPI, NPL>(c, g, splits);
-    if (layout == MM_NARROW) return launch_mm_t<2, 2, 4, 1, 2, 2, EPI, NPL>(c, g, splits);
+    if (layout == MM_NARROW) {
+        // gate/up (no k-split, 65 to 128 rows) streams the most weights per workgroup: a ring of two chunks with the
+        // activations staged as deep (96 rows: 72.8 -> 65.8 us; the split products measured no gain from it)
+        if (EPI == EPI_SWIGLU) return launch_mm_t<2, 2, 4, 1, 2, 4, EPI, NPL, true>(c, g, splits);
+        return launch_mm_t<2, 2, 4, 1, 2, 2, EPI, NPL>(c, g, splits);
+    }
     return launch_mm_t<2, 2, 8, 1, 2, 2, EPI, NPL>(c, g, splits);
 }
 // Wh: the half-precision tiles, or null for the two-term product on the bf16 tiles already in g.Wt
