@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from conftest import have_gpu
-from parity import (OracleSide, record, TOL_BF16, TOL_BF16_MANY, TOL_F32, check_invariants, compare_stream, row_rel_err, to_host_weights)
+from parity import (OracleSide, StreamInputs, record, TOL_BF16, TOL_BF16_MANY, TOL_F32, check_invariants, compare_stream, row_rel_err, to_host_weights)
 from paper_2604_17701_amd import binding
 from wisv_inputs import configs, gen
 from wisv_inputs.configs import PROTO_FH, PROTO_SH
@@ -375,6 +375,51 @@ def test_many_rows_precision_classes(one_term):
     w = replace(configs.get(3), model=MID128, batch=9, ctx=40, k=8, protos=protos, kv_source="prefill",
                 name=f"mid128_b9_l40_k8_terms{one_term}", index=18, taus=(0.5,))
     _run_workload(w, TOL_BF16, kv="prefill", one_term=one_term)
+
+
+def test_precision_classes_and_row_counts_switch_on_one_ctx():
+    """Beyond 16 rows every activation buffer is written only in the representation its consumer reads, and which
+    one that is follows the precision option.  On one ctx, rounds with fresh random drafts alternate between option
+    values and between 72 and 16 rows; a product that read a plane left behind by an earlier round would miss the
+    oracle, which recomputes every round from that round's drafts."""
+    protos = (PROTO_FH,) * 9
+    w = replace(configs.get(3), model=MID128, batch=9, ctx=40, k=8, protos=protos, kv_source="prefill",
+                name="mid128_b9_l40_k8_switching", index=19, taus=(0.5,))
+    dev = torch.device("cuda:0")
+    wd = gen.make_weights(w.model, w.seed, dev)
+    side = OracleSide(w, to_host_weights(wd))
+    ctx = _ctx(w, wd)
+    for b in range(w.batch):
+        ctx.wisv_prefill(b, gen.context_tokens(w, b))
+        side.prefill(b)
+    default = ctx.wisv_get_option(binding.WISV_OPT_ONE_TERM_CLASSES)
+    csi = gen.csi_features(w)
+    hds = [gen.draft_hidden(w, b) for b in range(w.batch)]
+    rng = np.random.default_rng(19)
+    steps = [(default, 9), (0, 9), (binding.WISV_TERM_ALL, 9), (default, 2), (binding.WISV_TERM_QKV | binding.WISV_TERM_O, 9),
+             (default, 9)]
+    flags = binding.WISV_FLAG_NO_COMMIT | binding.WISV_FLAG_KEEP_LOGITS
+    stats = {}
+    for step, (mask, nb) in enumerate(steps):
+        ctx.wisv_set_option(binding.WISV_OPT_ONE_TERM_CLASSES, mask)
+        tol = TOL_BF16 if mask == 0 or nb * w.k <= 16 else TOL_BF16_MANY
+        drafts = rng.integers(0, w.model.vocab, (nb, w.k)).astype(np.int32)
+        drafts[:, 0] = [side.pred_next[b] for b in range(nb)]          # a block starts at the pending token
+        sub = replace(w, batch=nb, protos=protos[:nb])
+        hd, row_map = gen.pack_hidden(sub, hds[:nb], [list(range(w.k))] * nb)
+        g = ctx.wisv_verify_round(np.arange(nb), drafts.reshape(-1), protos[:nb], hd, row_map, csi[:nb], np.full(nb, 0.5),
+                                  w.k, flags)
+        check_invariants(g, drafts.reshape(-1), w.k)
+        logits = ctx.wisv_debug_copy(binding.WISV_DBG_LOGITS, nb * w.k)
+        for b in range(nb):
+            si = StreamInputs(drafts[b], hds[b], side.pred_next[b], list(range(w.k)))
+            o = side.round(b, si, PROTO_FH, hd, row_map[b * w.k:(b + 1) * w.k], csi[b], 0.5, want_logits=True)
+            err = row_rel_err(logits[b * w.k:(b + 1) * w.k], o["logits"])
+            stats[f"logit_rel_step{step}"] = max(stats.get(f"logit_rel_step{step}", 0.0), err)
+            assert err <= tol.logit_rel, f"step {step} (classes {mask}, {nb} streams): logits rel err {err}"
+            compare_stream(g, b, o, w.k, 0.5, tol, stats, logits[b * w.k:(b + 1) * w.k])
+    record(w.name, stats)
+    ctx.wisv_destroy()
 
 
 def test_precision_option_is_refused_where_it_cannot_apply():
