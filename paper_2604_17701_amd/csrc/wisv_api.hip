@@ -422,6 +422,11 @@ extern "C" const char *wisv_last_error(const wisv_ctx *ctx) { return ctx ? ctx->
 
 // Enqueues the decoder over f.rows rows (Alg. 1 "Verify"): leaves h^T in c->h_t and the greedy token of
 // every row in c->amax.
+// The folded RMSNorms make every workgroup of the consuming product sum the slices (or stage the whole attention row)
+// itself, work that grows with the rows while the launch it saves does not.  At the 8B shape, one stream over 512
+// cached tokens: 4 rows 3.43 -> 3.38 ms per round with the folds; 8 rows 3.52 -> 3.72 ms, 16 rows 3.84 -> 4.14 ms.
+constexpr int FOLD_MAX_ROWS = 4;
+
 static void enqueue_forward(Ctx *c, const Fwd &f) {
     const wisv_config &g = c->cfg;
     const int d = g.d_model, F = g.d_ff;
@@ -479,11 +484,11 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
         const bool fuse_rope = attn_mfma_fuses_rope(c, f);
         for (int l = 0; l < g.n_layers; ++l) {
             const LayerW &L = c->layers[l];
-            // At most 16 rows, attention with the fused prologue: the attention norm is folded into the QKV product
+            // Few rows, attention with the fused prologue: the attention norm is folded into the QKV product
             // (it sums the previous slices into the residual stream itself and is fed x * gain) and the attention
             // prologue, which sums the QKV slices anyway, applies 1 / rms.  One launch less per layer.
             int nq = 0, n_ss = 0;
-            if (fuse_rope && f.rows <= 16) {
+            if (fuse_rope && f.rows <= FOLD_MAX_ROWS) {
                 nq = n_ss = launch_gemm_ws_normfold(c, L.wqkv_t, c->x, c->x_alt, ny, L.attn_norm, c->qkv, qs, MAX_SPLITS, f.rows,
                                                     c->d_qkv, d, c->ss, KC_GEMM_QKV);
                 if (nq) std::swap(c->x, c->x_alt);
@@ -501,11 +506,11 @@ static void enqueue_forward(Ctx *c, const Fwd &f) {
                 if (!launch_attn_mfma(c, f, l, 0)) launch_attn_ref(c, f, l);
             }
             ny = 0;
-            // At most 16 rows: the O projection keeps its k-split inside the workgroup, adds the residual stream itself
+            // Few rows: the O projection keeps its k-split inside the workgroup, adds the residual stream itself
             // and hands x * gain and the rows' sums of squares to gate/up, which applies 1 / rms: the FFN norm's launch
             // goes too.  It takes the attention's k-split partials as they are when there are few of them.
             int n_ss2 = 0;
-            if (f.rows <= 16) {
+            if (f.rows <= FOLD_MAX_ROWS) {
                 const AttnPartials ap{c->att_o, c->att_m, c->att_l, att_splits, f.rows, g.n_heads};
                 const bool partials = defer && att_splits > 1;
                 if (!partials || att_splits <= WS_PRO_SPLITS)

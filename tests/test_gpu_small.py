@@ -438,10 +438,11 @@ def test_precision_option_is_refused_where_it_cannot_apply():
     ctx.wisv_destroy()
 
 
-@pytest.mark.parametrize("batch,k", [(1, 4), (2, 4), (1, 7)])
+@pytest.mark.parametrize("batch,k", [(1, 4), (2, 2), (1, 3), (4, 1), (2, 4), (1, 7)])
 def test_small_bf16_decoder_folded_norms(batch, k):
-    """At most 8 rows and few attention splits: both RMSNorms of a layer are folded into the products around them
-    (QKV with the attention prologue; the O projection with gate/up), on a decoder with a power-of-two FFN width."""
+    """At most 4 rows and few attention splits: both RMSNorms of a layer are folded into the products around them
+    (QKV with the attention prologue; the O projection with gate/up), on a decoder with a power-of-two FFN width;
+    the same decoder with 8 and 7 rows takes the norm kernels."""
     model = replace(MID128, d_ff=2048)
     protos = tuple(PROTO_FH if b % 2 == 0 else PROTO_SH for b in range(batch))
     w = replace(configs.get(1), model=model, batch=batch, ctx=150, k=k, protos=protos, kv_source="prefill",
