@@ -501,12 +501,14 @@ static int attn_splits(const Ctx *c, const Fwd &f) {
     return std::max(1, std::min(std::min(want, 16), c->att_max_splits));   // 16: one batch of the combine kernel
 }
 
-// With several k-splits every split repeats the query part of the prologue: worth it while a round is a chain of
-// short kernels (at most 16 rows; 4.04 -> 3.92 ms at 8 rows over 4096 cached tokens), not once the slices of many
-// rows would be read by every split (96 rows, 4 splits: the attention kernel loses what the saved launch gains).
+// With several k-splits every split repeats the query part of the prologue (it sums the QKV slices of its queries
+// and rotates them; the split that ends the sequence also appends).  Worth it while a round is a chain of short
+// kernels (at most 16 rows; 4.04 -> 3.92 ms at 8 rows over 4096 cached tokens) and, with more rows, up to four splits:
+// 96 rows, 2 splits 6.34 -> 6.15 ms per round; 72 rows, 3 splits 6.25 -> 6.09; 32 rows, 4 splits 4.70 -> 4.66;
+// 80 rows over 4096 tokens, 4 splits 6.75 -> 6.74.  More splits of many rows go through k_rope_append.
 bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f) {
     const int s = attn_splits(c, f);
-    return s == 1 || (s > 1 && f.rows <= 16);
+    return s >= 1 && (f.rows <= 16 || s <= 4);
 }
 
 // c->o from the k-split partials in c->att_o / att_m / att_l

@@ -495,13 +495,22 @@ def test_repeated_device_round_replays_match_the_eager_round():
     ctx.wisv_destroy()
 
 
-@pytest.mark.parametrize("lengths,k", [((7, 300, 45), 4), ((520, 31, 33, 64), 3), ((1000, 2), 8)])
+@pytest.mark.parametrize("lengths,k", [
+    ((7, 300, 45), 4), ((520, 31, 33, 64), 3), ((1000, 2), 8),          # at most 16 rows
+    ((300, 200, 77), 7),                  # 21 rows, two splits, two query tiles
+    ((700, 20, 333), 6),                  # 18 rows, three splits
+    ((700, 300, 45, 1000, 64), 6),        # 30 rows, four splits
+    ((500, 31, 260), 12),                 # 36 rows, four splits, three query tiles (four waves per workgroup)
+    ((400, 90), 16),                      # 32 rows, four splits, four query tiles
+    ((2000, 130, 64, 999), 5),            # 20 rows, eight splits: RoPE and the append in a kernel of their own
+])
 def test_mixed_context_lengths_in_one_round(lengths, k):
-    """Streams of very different cached lengths in one round of at most 16 rows on the MFMA attention path: the
-    k-split attention (which does RoPE and the append itself) gives the tail of every stream to its last split,
-    leaves splits of short streams empty, and the O projection (or the combine kernel) merges what is there.
-    Every stream is prefilled for real on both sides and compared with the oracle."""
+    """Streams of very different cached lengths in one round on the MFMA attention path: the k-split attention
+    (which does RoPE and the append itself at up to 16 rows, and with up to four splits beyond) gives the tail of
+    every stream to its last split, leaves splits of short streams empty, and the O projection (or the combine
+    kernel) merges what is there.  Every stream is prefilled for real on both sides and compared with the oracle."""
     batch = len(lengths)
+    tol = TOL_BF16 if batch * k <= 16 else TOL_BF16_MANY
     base = replace(configs.get(3), model=MID128, batch=batch, ctx=max(lengths), k=k, protos=(PROTO_FH,) * batch,
                    kv_source="prefill", name=f"mid128_mixed_{'_'.join(map(str, lengths))}_k{k}", index=23, taus=(0.5,))
     dev = torch.device("cuda:0")
@@ -532,7 +541,7 @@ def test_mixed_context_lengths_in_one_round(lengths, k):
         o = sides[b].round(b, ins[b], PROTO_FH, hd, row_map[rows], csi[b], 0.5, want_logits=True)
         err = row_rel_err(logits[rows], o["logits"])
         stats["logit_rel"] = max(stats.get("logit_rel", 0.0), err)
-        assert err <= TOL_BF16.logit_rel, (b, err)
-        compare_stream(g, b, o, k, 0.5, TOL_BF16, stats, logits[rows])
+        assert err <= tol.logit_rel, (b, err)
+        compare_stream(g, b, o, k, 0.5, tol, stats, logits[rows])
     record(base.name, stats)
     ctx.wisv_destroy()
