@@ -488,28 +488,27 @@ template <int NQ, int NW, bool FUSE> static bool launch_nq(Ctx *c, const AttnArg
 }
 
 // One workgroup per (stream, KV head) when that fills the chip (then the workgroup writes the output itself);
-// otherwise k-splits of at least one 32-key step per wave, up to one workgroup per CU and 16 in all (16 streams x
-// 8 KV heads over 2048 cached tokens: 2 splits 33.5 us, 4 splits 40.8 us; one stream over 512: the round takes
-// 3.51 ms with 3 splits and their combine kernel, 3.55 ms with one).  0: the shape is not served.
+// otherwise k-splits of at least one 32-key step per wave, never more workgroups than CUs (a second round of
+// workgroups costs more than the splits gain: 12 streams x 8 KV heads over 2048 cached tokens, 3 splits = 288
+// workgroups 44.7 us, 2 splits 29.1 us; 24 streams over 4096: 2 splits 112.8 us, 1 split 98.7 us) and 16 in all
+// (one stream over 512: the round takes 3.51 ms with 3 splits and their combine kernel, 3.55 ms with one).
+// 0: the shape is not served.
 static int attn_splits(const Ctx *c, const Fwd &f) {
     const wisv_config &g = c->cfg;
     const int rep = g.n_heads / g.n_kv_heads, R = rep * f.k;
     if (!c->bf16 || g.head_dim != HD || R > 64 || f.rows != f.batch * f.k) return 0;
     const int nw = R <= 32 ? 8 : 4;
     const int n_steps = (f.max_len_ub + STEP - 1) / STEP, wgs = f.batch * g.n_kv_heads;
-    const int want = wgs >= 256 ? 1 : std::min((256 + wgs - 1) / wgs, (n_steps + nw - 1) / nw);
+    const int want = std::max(1, std::min(256 / wgs, (n_steps + nw - 1) / nw));
     return std::max(1, std::min(std::min(want, 16), c->att_max_splits));   // 16: one batch of the combine kernel
 }
 
 // With several k-splits every split repeats the query part of the prologue (it sums the QKV slices of its queries
-// and rotates them; the split that ends the sequence also appends).  Worth it while a round is a chain of short
-// kernels (at most 16 rows; 4.04 -> 3.92 ms at 8 rows over 4096 cached tokens) and, with more rows, up to four splits:
-// 96 rows, 2 splits 6.34 -> 6.15 ms per round; 72 rows, 3 splits 6.25 -> 6.09; 32 rows, 4 splits 4.70 -> 4.66;
-// 80 rows over 4096 tokens, 4 splits 6.75 -> 6.74.  More splits of many rows go through k_rope_append.
-bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f) {
-    const int s = attn_splits(c, f);
-    return s >= 1 && (f.rows <= 16 || s <= 4);
-}
+// and rotates them; the split that ends the sequence also appends).  That always beat or equalled a kernel of its own
+// for RoPE and the append: 8 rows over 4096 cached tokens 4.04 -> 3.92 ms per round; 96 rows, 2 splits 6.34 -> 6.15;
+// 72 rows, 3 splits 6.25 -> 6.09; 32 rows over 4096 tokens, 8 splits 4.98 -> 4.86; 24 rows over 8192 tokens, 16
+// splits 4.88 -> 4.89.  k_rope_append serves the shapes this kernel does not take.
+bool attn_mfma_fuses_rope(const Ctx *c, const Fwd &f) { return attn_splits(c, f) >= 1; }
 
 // c->o from the k-split partials in c->att_o / att_m / att_l
 void launch_attn_combine(Ctx *c, const Fwd &f, int n_splits) {
