@@ -880,8 +880,8 @@ static bool launch_mm_t(Ctx *c, GemmArgs &g, int splits) {
 // Beyond: tiles of 128 rows, met by 4 x 2 waves (256 weight rows per workgroup, every weight tile loaded by two
 // waves), or - "wide" - by 8 x 1 waves with four row tiles each (512 weight rows, half the L2 traffic per flop,
 // but half as many workgroups), or - "narrow" - by 2 x 2 waves (128 weight rows; two workgroups share a CU).
-// Wide pays when it still fills the chip (>= 200 workgroups) and, with k-splits, a split keeps >= 24 k-tiles;
-// narrow when a product without k-splits would otherwise leave CUs idle.
+// With k-splits wide pays when it still fills the chip (>= 200 workgroups) and a split keeps >= 24 k-tiles; without
+// them the shape with the fewest rounds of workgroups, weighted by what a round of that shape costs, is taken.
 // A product without k-splits over at most 64 rows and few row-blocks (gate/up) would fill a quarter of the chip
 // that way: "k-slice" workgroups cover 128 weight rows only and their waves split each chunk's k-tiles among them
 // (98.9 -> 50.5 us at 32 rows, 116.9 -> 76.8 us at 64).  Beyond 64 rows workgroups that narrow re-read the
@@ -897,7 +897,15 @@ static int mm_layout(int rows, int nrb, int nkt, bool can_split, int max_splits)
     if (rows <= 64) return MM_NORMAL;
     const int tiles = (rows + 127) / 128;
     const int base8 = ((nrb + 8 * MM_RB - 1) / (8 * MM_RB)) * tiles, base4 = ((nrb + 4 * MM_RB - 1) / (4 * MM_RB)) * tiles;
-    if (!can_split) return base8 >= 200 ? MM_WIDE : base4 >= 200 ? MM_NORMAL : MM_NARROW;
+    if (!can_split) {
+        // A workgroup takes about the same time however many of them run, so the cost is rounds of 256 workgroups
+        // times the time of one round, measured on gate/up at the 8B shape: wide 118 us (512 rows), 4 x 2 waves
+        // 88 us (256 rows), narrow 67 us (128 rows).  384 rows: 336 workgroups of 4 x 2 waves took 154 us where 168
+        // wide ones take one round.
+        const int base2 = ((nrb + 2 * MM_RB - 1) / (2 * MM_RB)) * tiles;
+        const double c8 = (base8 + 255) / 256 * 1.34, c4 = (base4 + 255) / 256 * 1.0, c2 = (base2 + 255) / 256 * 0.76;
+        return c8 <= c4 && c8 <= c2 ? MM_WIDE : c4 <= c2 ? MM_NORMAL : MM_NARROW;
+    }
     const int s = std::max(1, std::min(256 / std::max(1, base8), max_splits));
     return base8 * s >= 200 && nkt / s >= 24 ? MM_WIDE : MM_NORMAL;
 }
