@@ -234,12 +234,13 @@ def test_config1_shape_speculative_sampling_round(target8b):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("batch,k", [(8, 4), (8, 8), (1, 16), (1, 12), (2, 8)])
+@pytest.mark.parametrize("batch,k", [(8, 4), (8, 8), (1, 16), (1, 12), (2, 8), (20, 8), (37, 8)])
 def test_8b_shape_mid_row_counts(target8b, batch, k):
     """32 and 64 rows at the 8B shape: the row counts between the weight-streaming kernel (at most 16 rows) and the
     128-row tiles, where gate/up runs in the k-slice layout of the many-rows kernel.  12 and 16 rows: the
     weight-streaming kernel at its largest row counts (no folded norms) with three and four query tiles per KV head
-    in the attention kernel, and two streams of eight drafts."""
+    in the attention kernel, and two streams of eight drafts.  160 and 296 rows: the 128-row tiles with a ragged last
+    tile, in the 4 x 2-wave and in the wide workgroup shape."""
     w = configs.Workload(f"mid_8b_b{batch}_l256_k{k}", 1, configs.get(1).model, batch=batch, ctx=256, k=k,
                          protos=tuple(PROTO_FH if b % 2 == 0 else PROTO_SH for b in range(batch)), match_rate=(0.4, 0.9))
     _run(w, target8b, sampled=[min(3, batch - 1)])
